@@ -1,0 +1,155 @@
+/*
+ * hisa.h -- C ABI of the HISA hierarchical indexer for AMD MI355X (gfx950).
+ *
+ * The library computes, per query t, the token-index set that Sparse MLA consumes, by the
+ * two-stage search of the HISA paper (Section 4.1, Algorithm 1), and the flat DSA indexer
+ * (Section 3, Eqs. 1-2) as the baseline at the same shapes.
+ *
+ * Conventions for every call
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller, row-major, densely packed.
+ *     The descriptor structs themselves live in HOST memory.
+ *   - The library allocates nothing and keeps no state.  Scratch memory is a caller-provided
+ *     device workspace `ws` of `ws_bytes` bytes (256-byte aligned); hisa_workspace_bytes() gives
+ *     the size a call wants.  A call may be given more; it never touches bytes past ws_bytes.
+ *   - A call only enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = the null
+ *     stream) and returns without synchronising.  Calls sharing one workspace must be ordered on
+ *     one stream.
+ *   - Return value: HISA_OK, or an error code.  Validation is done on the host BEFORE anything is
+ *     launched: on an error other than HISA_ERR_LAUNCH nothing was enqueued and outputs are
+ *     untouched.  Device-resident arrays (seq_len, q_seq, q_pos, block_idx) cannot be validated
+ *     on the host; kernels clamp positions to the sequence length so a bad value cannot cause an
+ *     out-of-bounds access, but the result for that query is then unspecified.
+ *   - Positions are 0-based.  The query at position p sees keys s <= p of its own sequence
+ *     (Section 4.1, boundary behaviour: a prefix no longer than k is selected whole).
+ *   - Top-k / top-m order candidates by score descending, ties by lower index.  Index outputs
+ *     hold the selected ids in ASCENDING order, then -1 padding when fewer than k (m) exist.
+ *
+ * Supported shapes
+ *   - q F32  + k F32  (+ pooled F32):  any H <= 128, d % 4 == 0, d <= 512  (plain fp32 ALU path)
+ *   - q BF16 + k BF16 or FP8_E4M3 (+ pooled BF16):  d == 128, H in {32, 64}, B % 32 == 0
+ *     (MFMA path, fp32 accumulation; fp8 keys are widened to bf16 exactly and the per-token scale
+ *     multiplies the finished score, which equals Eq. 1 on the dequantised key because the scale
+ *     is positive).
+ *   - top-k / candidate limits: k <= 8192, m <= 1024, m * B <= 65536.
+ */
+#ifndef HISA_H_
+#define HISA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HISA_OK = 0,
+  HISA_ERR_NULL = 1,        /* a required pointer is NULL                                        */
+  HISA_ERR_SHAPE = 2,       /* H, d, B, m, k, T, s_max outside the supported set                 */
+  HISA_ERR_DTYPE = 3,       /* unsupported dtype or dtype combination                            */
+  HISA_ERR_INFEASIBLE = 4,  /* m * B < k (Section 4.1, feasibility constraint) or m < 2          */
+  HISA_ERR_WORKSPACE = 5,   /* ws is NULL or smaller than the call's minimum                     */
+  HISA_ERR_ALIGN = 6,       /* a tensor pointer is not 16-byte aligned                           */
+  HISA_ERR_LAUNCH = 7       /* the HIP runtime refused a launch (hipGetLastError was non-zero)   */
+} hisa_status;
+
+typedef enum {
+  HISA_F32 = 0,
+  HISA_BF16 = 1,
+  HISA_FP8_E4M3 = 2         /* OCP e4m3fn codes + one fp32 scale per token                       */
+} hisa_dtype;
+
+/* Token-level indexing keys k_s (Section 3): n_seq sequences padded to s_max rows each. */
+typedef struct {
+  const void*    k;         /* [n_seq, s_max, d] of k_dtype (device)                             */
+  const float*   k_scale;   /* [n_seq, s_max] fp32, required iff k_dtype == FP8: key = scale*code */
+  const int32_t* seq_len;   /* [n_seq] valid keys per sequence (device)                          */
+  int32_t        n_seq;
+  int32_t        s_max;
+  int32_t        d;
+  int32_t        k_dtype;   /* hisa_dtype */
+} hisa_keys;
+
+/* Indexing queries q_{t,j} and gates w_{t,j} (Section 3) for T packed queries. */
+typedef struct {
+  const void*    q;         /* [T, H, d] of q_dtype (device)                                     */
+  const float*   w;         /* [T, H] fp32 gates, any sign (device)                              */
+  const int32_t* q_seq;     /* [T] sequence id of each query, or NULL: all queries in sequence 0 */
+  const int32_t* q_pos;     /* [T] position of each query, or NULL: q_pos[t] = q_pos0 + t        */
+  int32_t        T;
+  int32_t        H;
+  int32_t        q_pos0;
+  int32_t        q_dtype;   /* hisa_dtype: F32 or BF16 */
+} hisa_queries;
+
+/* Operation selector for hisa_workspace_bytes. */
+enum { HISA_OP_POOL = 0, HISA_OP_BLOCK_SCORE_TOPK = 1, HISA_OP_TOKEN_REFINE_TOPK = 2,
+       HISA_OP_FLAT_TOPK = 3 };
+
+/*
+ * Block pooling (Eq. 4; Algorithm 1, pooling loop): pooled[n, b, :] = mean of the keys of block
+ * b of sequence n, for b in [blk_begin, blk_end) (blk_end <= s_max / B; pass 0, s_max / B for all).
+ * A block holds tokens bB .. min((b+1)B, seq_len[n]) - 1 and is averaged over the tokens present;
+ * a block with no token is written as zeros.  Accumulation in fp32, one rounding to pooled_dtype
+ * (F32, or BF16 for BF16/FP8 keys).  pooled: [n_seq, s_max / B, d] device, written in the given
+ * block range only.  Needs no workspace.
+ */
+int hisa_pool_blocks(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_t blk_end,
+                     void* pooled, int32_t pooled_dtype, void* stream);
+
+/*
+ * Stage 1 (Eqs. 5-6; Algorithm 1, block-level coarse filter).  For each query, scores the pooled
+ * keys of the visible blocks 0 .. b_t (b_t = q_pos / B) and keeps min(m, b_t + 1) blocks: block 0
+ * and block b_t always (Section 4.1: first and last block forced, counted inside the budget m),
+ * the rest by score.  `keys` supplies shapes and seq_len only (keys->k may be NULL).
+ *   pooled       [n_seq, s_max / B, d] of pooled_dtype (device, in)
+ *   block_idx    [T, m] int32 (device, out): kept block ids ascending, then -1
+ *   block_scores [T, s_max / B] fp32 (device, out) or NULL: J_{t,b} for b <= b_t, -inf beyond
+ * Workspace: T * round_up(s_max / B, 64) floats when block_scores is NULL, else none.
+ */
+int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, const void* pooled,
+                          int32_t pooled_dtype, int32_t B, int32_t m, int32_t* block_idx,
+                          float* block_scores, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Stage 2 (Eqs. 7-9; Algorithm 1, token-level refinement).  Scores, with Eq. 1, the visible
+ * tokens of the kept blocks and selects the k best.
+ *   block_idx   [T, m] int32 (device, in): ascending block ids then -1, as Stage 1 writes them
+ *   topk_idx    [T, k] int32 (device, out): selected token positions (within the query's
+ *               sequence) ascending, then -1
+ *   topk_scores [T, k] fp32 (device, out) or NULL: scores aligned with topk_idx (padding: -inf)
+ *   cand_scores [T, m * B] fp32 (device, out) or NULL: every candidate score, slot c = kept block
+ *               c / B, offset c % B; -inf where masked.  Requesting it selects the two-kernel path.
+ * Workspace: none for the fused path (cand_scores NULL, T >= 256, m * B <= 16384), otherwise
+ * T * m * B floats unless cand_scores is given.
+ */
+int hisa_token_refine_topk(const hisa_queries* queries, const hisa_keys* keys, int32_t B, int32_t m,
+                           const int32_t* block_idx, int32_t k, int32_t* topk_idx,
+                           float* topk_scores, float* cand_scores, void* ws, size_t ws_bytes,
+                           void* stream);
+
+/*
+ * Flat DSA indexer (Eqs. 1-2): scores every visible key s <= q_pos and selects the k best.
+ * Same outputs as Stage 2.  Queries are processed in chunks sized to the workspace:
+ * minimum 8 * round_up(s_max, 64) floats (+ the merge area, see hisa_workspace_bytes).
+ */
+int dsa_flat_indexer_topk(const hisa_queries* queries, const hisa_keys* keys, int32_t k,
+                          int32_t* topk_idx, float* topk_scores, void* ws, size_t ws_bytes,
+                          void* stream);
+
+/* Recommended workspace size in bytes for `op` (HISA_OP_*) at these shapes; 0 if none is needed
+ * or the shapes are invalid.  `want_scores` != 0: the optional full score output of Stage 1 / 2
+ * is requested (which then replaces the workspace). */
+size_t hisa_workspace_bytes(int op, const hisa_queries* queries, const hisa_keys* keys, int32_t B,
+                            int32_t m, int32_t k, int32_t want_scores);
+
+/* Static description of a status code. */
+const char* hisa_status_string(int status);
+
+/* Library version, "major.minor". */
+const char* hisa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HISA_H_ */

@@ -1,0 +1,457 @@
+// Host side of the C ABI declared in include/hisa.h: argument validation, workspace carving and
+// kernel launches.  Nothing here allocates or synchronises.
+#include "../../include/hisa.h"
+
+#include <hip/hip_runtime.h>
+
+#include "hisa_kernels.h"
+
+using namespace hisa;
+
+namespace {
+
+inline long round_up(long x, long a) { return (x + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int launch_status() { return hipGetLastError() == hipSuccess ? HISA_OK : HISA_ERR_LAUNCH; }
+
+constexpr int kMaxK = 8192, kMaxM = 1024, kMaxCand = 65536, kSeg = 65536;
+
+enum Path { PATH_NONE = 0, PATH_F32 = 1, PATH_MFMA = 2 };
+
+// Which arithmetic path a dtype combination takes (see "Supported shapes" in hisa.h).
+int pick_path(int q_dtype, int k_dtype, int H, int d, int* status) {
+  if (q_dtype == HISA_F32 && k_dtype == HISA_F32) {
+    if (H < 1 || H > 128 || d < 4 || d > 512 || d % 4) { *status = HISA_ERR_SHAPE; return PATH_NONE; }
+    return PATH_F32;
+  }
+  if (q_dtype == HISA_BF16 && (k_dtype == HISA_BF16 || k_dtype == HISA_FP8_E4M3)) {
+    if (d != 128 || (H != 32 && H != 64)) { *status = HISA_ERR_SHAPE; return PATH_NONE; }
+    return PATH_MFMA;
+  }
+  *status = HISA_ERR_DTYPE;
+  return PATH_NONE;
+}
+
+int check_queries(const hisa_queries* q) {
+  if (!q || !q->q || !q->w) return HISA_ERR_NULL;
+  if (q->T < 1 || q->H < 1) return HISA_ERR_SHAPE;
+  if (!aligned16(q->q)) return HISA_ERR_ALIGN;
+  return HISA_OK;
+}
+
+int check_keys(const hisa_keys* k, bool need_data) {
+  if (!k || !k->seq_len) return HISA_ERR_NULL;
+  if (k->n_seq < 1 || k->s_max < 1 || k->d < 1) return HISA_ERR_SHAPE;
+  if (k->k_dtype < HISA_F32 || k->k_dtype > HISA_FP8_E4M3) return HISA_ERR_DTYPE;
+  if (need_data) {
+    if (!k->k) return HISA_ERR_NULL;
+    if (k->k_dtype == HISA_FP8_E4M3 && !k->k_scale) return HISA_ERR_NULL;
+    if (!aligned16(k->k)) return HISA_ERR_ALIGN;
+  }
+  return HISA_OK;
+}
+
+ScoreArgs base_args(const hisa_queries* q, const hisa_keys* k) {
+  ScoreArgs a{};
+  a.q = q->q;
+  a.w = q->w;
+  a.q_seq = q->q_seq;
+  a.q_pos = q->q_pos;
+  a.q_pos0 = q->q_pos0;
+  a.H = q->H;
+  a.d = k->d;
+  a.keys = k->k;
+  a.k_scale = k->k_dtype == HISA_FP8_E4M3 ? k->k_scale : nullptr;
+  a.seq_len = k->seq_len;
+  a.n_seq = k->n_seq;
+  a.rows_per_seq = k->s_max;
+  a.pos_div = 1;
+  a.block_idx = nullptr;
+  a.m = 0;
+  a.B = 1;
+  a.tiles_per_wave = 1;
+  return a;
+}
+
+// ---- scoring launches -------------------------------------------------------------------
+template <int KDT>
+void launch_ranges_mfma(const ScoreArgs& a, int n_tiles_max, hipStream_t st) {
+  const int groups = (n_tiles_max + 4 * a.tiles_per_wave - 1) / (4 * a.tiles_per_wave);
+  dim3 grid(groups, a.t_count);
+  if (a.H == 64)
+    hipLaunchKernelGGL((k_score_ranges<2, KDT>), grid, dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL((k_score_ranges<1, KDT>), grid, dim3(256), 0, st, a);
+}
+
+template <int KDT>
+void launch_prefill_mfma(const ScoreArgs& a, hipStream_t st) {
+  dim3 grid((a.t_count + 7) / 8);
+  if (a.H == 64)
+    hipLaunchKernelGGL((k_score_prefill<2, KDT>), grid, dim3(512), 0, st, a);
+  else
+    hipLaunchKernelGGL((k_score_prefill<1, KDT>), grid, dim3(512), 0, st, a);
+}
+
+// Scores `a.t_count` queries against up to n_rows_max rows each (flat / Stage 1: rows of the
+// key array; gather: m*B slots).  key_dt is the dtype of the rows.
+void launch_score(int path, int key_dt, ScoreArgs a, long n_rows_max, bool consecutive,
+                  hipStream_t st) {
+  if (path == PATH_F32) {
+    const int per_wg = 1024;
+    dim3 grid((unsigned)((n_rows_max + per_wg - 1) / per_wg), a.t_count);
+    const size_t sh = ((size_t)a.H * a.d + a.H) * sizeof(float);
+    hipLaunchKernelGGL(k_score_ranges_f32, grid, dim3(256), sh, st, a, per_wg);
+    return;
+  }
+  const bool gather = a.block_idx != nullptr;
+  if (!gather && consecutive && a.t_count >= 64) {
+    if (key_dt == HISA_BF16) launch_prefill_mfma<DT_BF16>(a, st);
+    else launch_prefill_mfma<DT_FP8>(a, st);
+    return;
+  }
+  const int n_tiles = (int)((n_rows_max + 31) / 32);
+  // few queries: spread one query's tiles over many workgroups; many queries: amortise the
+  // query-fragment load over more tiles
+  int tpw = a.t_count >= 1024 ? 8 : (a.t_count >= 128 ? 4 : 2);
+  if (gather) tpw = a.t_count >= 1024 ? 16 : 4;
+  a.tiles_per_wave = tpw;
+  if (key_dt == HISA_BF16) launch_ranges_mfma<DT_BF16>(a, n_tiles, st);
+  else launch_ranges_mfma<DT_FP8>(a, n_tiles, st);
+}
+
+// ---- selection launches -----------------------------------------------------------------
+template <int MAP>
+int launch_select(const SelectArgs& a, int rows, int n_max, hipStream_t st) {
+  dim3 grid(a.n_seg, rows);
+  if (n_max <= 512)
+    hipLaunchKernelGGL((k_select<64, 8, MAP>), grid, dim3(64), 0, st, a);
+  else if (n_max <= 2048)
+    hipLaunchKernelGGL((k_select<256, 8, MAP>), grid, dim3(256), 0, st, a);
+  else if (n_max <= 8192)
+    hipLaunchKernelGGL((k_select<256, 32, MAP>), grid, dim3(256), 0, st, a);
+  else if (n_max <= 16384)
+    hipLaunchKernelGGL((k_select<1024, 16, MAP>), grid, dim3(1024), 0, st, a);
+  else if (n_max <= 65536)
+    hipLaunchKernelGGL((k_select<1024, 64, MAP>), grid, dim3(1024), 0, st, a);
+  else
+    return HISA_ERR_SHAPE;
+  return HISA_OK;
+}
+
+SelectArgs select_base(const hisa_queries* q, const hisa_keys* k) {
+  SelectArgs s{};
+  s.q_seq = q->q_seq;
+  s.q_pos = q->q_pos;
+  s.seq_len = k->seq_len;
+  s.q_pos0 = q->q_pos0;
+  s.n_seq = k->n_seq;
+  s.pos_div = 1;
+  s.seg_len = 1 << 30;
+  s.n_seg = 1;
+  return s;
+}
+
+template <int HG, int KDT, int E>
+int launch_fused_hg(const ScoreArgs& a, int k, int32_t* topk_idx, float* topk_scores,
+                    hipStream_t st) {
+  const size_t sh = 4 * kTileChunks * 16 + (size_t)a.m * a.B * 4 + sizeof(SelectSmem<256, E>);
+  auto kern = k_refine_fused<HG, KDT, E>;
+  // more than 64 KB of LDS per workgroup has to be asked for explicitly
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh) != hipSuccess)
+    return HISA_ERR_LAUNCH;
+  hipLaunchKernelGGL(kern, dim3(a.t_count), dim3(256), sh, st, a, k, topk_idx, topk_scores);
+  return HISA_OK;
+}
+
+template <int KDT, int E>
+int launch_fused(const ScoreArgs& a, int k, int32_t* topk_idx, float* topk_scores, hipStream_t st) {
+  return a.H == 64 ? launch_fused_hg<2, KDT, E>(a, k, topk_idx, topk_scores, st)
+                   : launch_fused_hg<1, KDT, E>(a, k, topk_idx, topk_scores, st);
+}
+
+// Flat indexer: rows of queries scored per chunk, and the size of the segment-merge area.
+struct FlatPlan {
+  long ld;          // score row stride (floats)
+  int n_seg;        // segments per row when s_max > 65536
+  long per_query;   // workspace bytes per query in a chunk
+};
+
+FlatPlan flat_plan(const hisa_keys* k, int kk) {
+  FlatPlan p;
+  p.ld = round_up(k->s_max, 64);
+  p.n_seg = (int)((k->s_max + kSeg - 1) / kSeg);
+  p.per_query = p.ld * 4 + (p.n_seg > 1 ? (long)p.n_seg * kk * 8 : 0);
+  return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* hisa_status_string(int status) {
+  switch (status) {
+    case HISA_OK: return "ok";
+    case HISA_ERR_NULL: return "a required pointer is NULL";
+    case HISA_ERR_SHAPE: return "shape outside the supported set";
+    case HISA_ERR_DTYPE: return "unsupported dtype combination";
+    case HISA_ERR_INFEASIBLE: return "infeasible budgets: need m >= 2 and m*B >= k";
+    case HISA_ERR_WORKSPACE: return "workspace missing or too small";
+    case HISA_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
+    case HISA_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+const char* hisa_version(void) { return "0.1"; }
+
+int hisa_pool_blocks(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_t blk_end,
+                     void* pooled, int32_t pooled_dtype, void* stream) {
+  int st = check_keys(keys, true);
+  if (st) return st;
+  if (!pooled) return HISA_ERR_NULL;
+  if (B < 1 || keys->s_max % B) return HISA_ERR_SHAPE;
+  const int M = keys->s_max / B;
+  if (blk_begin < 0 || blk_end > M || blk_begin > blk_end) return HISA_ERR_SHAPE;
+  const int kd = keys->k_dtype, d = keys->d;
+  const int vec = kd == HISA_F32 ? 4 : (kd == HISA_BF16 ? 8 : 16);
+  if (d % vec || d / vec > 256) return HISA_ERR_SHAPE;
+  if (!((kd == HISA_F32 && pooled_dtype == HISA_F32) ||
+        (kd != HISA_F32 && (pooled_dtype == HISA_BF16 || pooled_dtype == HISA_F32))))
+    return HISA_ERR_DTYPE;
+  if (blk_begin == blk_end) return HISA_OK;
+  hipStream_t s = (hipStream_t)stream;
+  dim3 grid(blk_end - blk_begin, keys->n_seq);
+#define POOL(KD, PD)                                                                             \
+  hipLaunchKernelGGL((k_pool<KD, PD>), grid, dim3(256), 0, s, keys->k, keys->k_scale,            \
+                     keys->seq_len, (long)keys->s_max, d, B, blk_begin, pooled)
+  if (kd == HISA_F32) POOL(DT_F32, DT_F32);
+  else if (kd == HISA_BF16 && pooled_dtype == HISA_BF16) POOL(DT_BF16, DT_BF16);
+  else if (kd == HISA_BF16) POOL(DT_BF16, DT_F32);
+  else if (pooled_dtype == HISA_BF16) POOL(DT_FP8, DT_BF16);
+  else POOL(DT_FP8, DT_F32);
+#undef POOL
+  return launch_status();
+}
+
+int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, const void* pooled,
+                          int32_t pooled_dtype, int32_t B, int32_t m, int32_t* block_idx,
+                          float* block_scores, void* ws, size_t ws_bytes, void* stream) {
+  int st = check_queries(queries);
+  if (st) return st;
+  st = check_keys(keys, false);
+  if (st) return st;
+  if (!pooled || !block_idx) return HISA_ERR_NULL;
+  if (!aligned16(pooled)) return HISA_ERR_ALIGN;
+  if (B < 1 || keys->s_max % B) return HISA_ERR_SHAPE;
+  if (m < 2) return HISA_ERR_INFEASIBLE;
+  if (m > kMaxM) return HISA_ERR_SHAPE;
+  const int M = keys->s_max / B;
+  if (M > kMaxCand) return HISA_ERR_SHAPE;
+  // pooled keys play the part of the keys here
+  int path = pick_path(queries->q_dtype, pooled_dtype == HISA_F32 ? HISA_F32 : HISA_BF16, queries->H,
+                       keys->d, &st);
+  if (!path) return st;
+  if (pooled_dtype != HISA_F32 && pooled_dtype != HISA_BF16) return HISA_ERR_DTYPE;
+  const int T = queries->T;
+  float* J = block_scores;
+  if (!J) {
+    if (!ws || ws_bytes < (size_t)T * M * 4) return HISA_ERR_WORKSPACE;
+    J = (float*)ws;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  if (block_scores) {
+    const long n = (long)T * M;
+    hipLaunchKernelGGL(k_fill_f32, dim3((unsigned)((n + 255) / 256 > 4096 ? 4096 : (n + 255) / 256)),
+                       dim3(256), 0, s, J, n, -__builtin_inff());
+  }
+  ScoreArgs a = base_args(queries, keys);
+  a.keys = pooled;
+  a.k_scale = nullptr;
+  a.rows_per_seq = M;
+  a.pos_div = B;
+  a.out = J;
+  a.ld = M;
+  a.t_begin = 0;
+  a.t_count = T;
+  launch_score(path, pooled_dtype, a, M, !queries->q_seq && !queries->q_pos, s);
+
+  SelectArgs sa = select_base(queries, keys);
+  sa.scores = J;
+  sa.ld = M;
+  sa.pos_div = B;
+  sa.t_begin = 0;
+  sa.k = m;
+  sa.out_idx = block_idx;
+  sa.out_scores = nullptr;
+  st = launch_select<MAP_BLOCKS>(sa, T, M, s);
+  if (st) return st;
+  return launch_status();
+}
+
+int hisa_token_refine_topk(const hisa_queries* queries, const hisa_keys* keys, int32_t B, int32_t m,
+                           const int32_t* block_idx, int32_t k, int32_t* topk_idx,
+                           float* topk_scores, float* cand_scores, void* ws, size_t ws_bytes,
+                           void* stream) {
+  int st = check_queries(queries);
+  if (st) return st;
+  st = check_keys(keys, true);
+  if (st) return st;
+  if (!block_idx || !topk_idx) return HISA_ERR_NULL;
+  if (B < 1 || keys->s_max % B || k < 1 || k > kMaxK || m > kMaxM) return HISA_ERR_SHAPE;
+  if (m < 2 || (long)m * B < k) return HISA_ERR_INFEASIBLE;
+  if ((long)m * B > kMaxCand) return HISA_ERR_SHAPE;
+  int path = pick_path(queries->q_dtype, keys->k_dtype, queries->H, keys->d, &st);
+  if (!path) return st;
+  if (path == PATH_MFMA && B % 32) return HISA_ERR_SHAPE;
+  const int T = queries->T;
+  const int n_slots = m * B;
+  hipStream_t s = (hipStream_t)stream;
+
+  ScoreArgs a = base_args(queries, keys);
+  a.block_idx = block_idx;
+  a.m = m;
+  a.B = B;
+  a.t_begin = 0;
+  a.t_count = T;
+  a.ld = n_slots;
+
+  const bool fused = path == PATH_MFMA && !cand_scores && T >= 256 && n_slots <= 16384;
+  if (fused) {
+    a.out = nullptr;
+    const bool bf = keys->k_dtype == HISA_BF16;
+    if (n_slots <= 8192)
+      st = bf ? launch_fused<DT_BF16, 32>(a, k, topk_idx, topk_scores, s)
+              : launch_fused<DT_FP8, 32>(a, k, topk_idx, topk_scores, s);
+    else
+      st = bf ? launch_fused<DT_BF16, 64>(a, k, topk_idx, topk_scores, s)
+              : launch_fused<DT_FP8, 64>(a, k, topk_idx, topk_scores, s);
+    if (st) return st;
+    return launch_status();
+  }
+
+  float* C = cand_scores;
+  if (!C) {
+    if (!ws || ws_bytes < (size_t)T * n_slots * 4) return HISA_ERR_WORKSPACE;
+    C = (float*)ws;
+  }
+  a.out = C;
+  launch_score(path, keys->k_dtype, a, n_slots, false, s);
+
+  SelectArgs sa = select_base(queries, keys);
+  sa.scores = C;
+  sa.ld = n_slots;
+  sa.n_fixed = n_slots;
+  sa.block_idx = block_idx;
+  sa.m = m;
+  sa.B = B;
+  sa.t_begin = 0;
+  sa.k = k;
+  sa.out_idx = topk_idx;
+  sa.out_scores = topk_scores;
+  st = launch_select<MAP_CAND>(sa, T, n_slots, s);
+  if (st) return st;
+  return launch_status();
+}
+
+int dsa_flat_indexer_topk(const hisa_queries* queries, const hisa_keys* keys, int32_t k,
+                          int32_t* topk_idx, float* topk_scores, void* ws, size_t ws_bytes,
+                          void* stream) {
+  int st = check_queries(queries);
+  if (st) return st;
+  st = check_keys(keys, true);
+  if (st) return st;
+  if (!topk_idx) return HISA_ERR_NULL;
+  if (k < 1 || k > kMaxK) return HISA_ERR_SHAPE;
+  int path = pick_path(queries->q_dtype, keys->k_dtype, queries->H, keys->d, &st);
+  if (!path) return st;
+  const FlatPlan p = flat_plan(keys, k);
+  if ((long)p.n_seg * k > kMaxCand) return HISA_ERR_SHAPE;
+  const int T = queries->T;
+  if (!ws) return HISA_ERR_WORKSPACE;
+  long chunk = (long)(ws_bytes / (size_t)p.per_query);
+  if (chunk > T) chunk = T;
+  if (chunk >= 8) chunk = chunk / 8 * 8;
+  if (chunk < 1 || (chunk < 8 && chunk < T)) return HISA_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  float* scores = (float*)ws;
+  float* part_sc = (float*)((char*)ws + chunk * p.ld * 4);
+  int32_t* part_id = (int32_t*)((char*)part_sc + chunk * (long)p.n_seg * k * 4);
+  const bool consecutive = !queries->q_seq && !queries->q_pos;
+
+  for (long t0 = 0; t0 < T; t0 += chunk) {
+    const int tc = (int)((T - t0) < chunk ? (T - t0) : chunk);
+    ScoreArgs a = base_args(queries, keys);
+    a.out = scores;
+    a.ld = p.ld;
+    a.t_begin = (int)t0;
+    a.t_count = tc;
+    launch_score(path, keys->k_dtype, a, keys->s_max, consecutive, s);
+
+    SelectArgs sa = select_base(queries, keys);
+    sa.scores = scores;
+    sa.ld = p.ld;
+    sa.t_begin = (int)t0;
+    sa.k = k;
+    if (p.n_seg == 1) {
+      sa.out_idx = topk_idx + t0 * k;
+      sa.out_scores = topk_scores ? topk_scores + t0 * k : nullptr;
+      st = launch_select<MAP_FLAT>(sa, tc, keys->s_max, s);
+      if (st) return st;
+    } else {
+      // two levels: the k best of every 65536-key segment, then the k best of those
+      sa.seg_len = kSeg;
+      sa.n_seg = p.n_seg;
+      sa.out_idx = part_id;
+      sa.out_scores = part_sc;
+      st = launch_select<MAP_FLAT>(sa, tc, kSeg, s);
+      if (st) return st;
+      SelectArgs sm = select_base(queries, keys);
+      sm.scores = part_sc;
+      sm.idx_in = part_id;
+      sm.ld = (long)p.n_seg * k;
+      sm.n_fixed = p.n_seg * k;
+      sm.t_begin = (int)t0;
+      sm.k = k;
+      sm.out_idx = topk_idx + t0 * k;
+      sm.out_scores = topk_scores ? topk_scores + t0 * k : nullptr;
+      st = launch_select<MAP_PAIRS>(sm, tc, p.n_seg * k, s);
+      if (st) return st;
+    }
+  }
+  return launch_status();
+}
+
+size_t hisa_workspace_bytes(int op, const hisa_queries* queries, const hisa_keys* keys, int32_t B,
+                            int32_t m, int32_t k, int32_t want_scores) {
+  if (!queries || !keys || queries->T < 1 || keys->s_max < 1) return 0;
+  const size_t T = (size_t)queries->T;
+  switch (op) {
+    case HISA_OP_POOL:
+      return 0;
+    case HISA_OP_BLOCK_SCORE_TOPK:
+      if (B < 1 || keys->s_max % B || want_scores) return 0;
+      return round_up((long)(T * (size_t)(keys->s_max / B) * 4), 256);
+    case HISA_OP_TOKEN_REFINE_TOPK: {
+      if (B < 1 || m < 1 || want_scores) return 0;
+      const size_t n_slots = (size_t)m * B;
+      const bool mfma = queries->q_dtype == HISA_BF16;
+      if (mfma && T >= 256 && n_slots <= 16384) return 0;   // fused path
+      return round_up((long)(T * n_slots * 4), 256);
+    }
+    case HISA_OP_FLAT_TOPK: {
+      if (k < 1) return 0;
+      const FlatPlan p = flat_plan(keys, k);
+      long chunk = (4L << 30) / p.per_query;      // aim at <= 4 GiB
+      if (chunk < 8) chunk = 8;
+      if (chunk > (long)T) chunk = (long)T;
+      chunk = round_up(chunk, 8);
+      return (size_t)round_up(chunk * p.per_query, 256);
+    }
+    default:
+      return 0;
+  }
+}
+
+}  // extern "C"

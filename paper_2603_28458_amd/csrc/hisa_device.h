@@ -1,0 +1,403 @@
+// Device-side building blocks of the HISA indexer kernels (gfx950 / CDNA4, wave64).
+//
+//  * QFrag / score_tile: the query-heads x key-tile contraction of Eq. 1 / Eq. 5 of the paper on
+//    the 32x32x16 bf16 MFMA, with the ReLU, gate and head-sum epilogue in registers.
+//  * tile staging: a 32-key x 128-dim key tile in LDS as 512 16-byte chunks, XOR-swizzled so that
+//    both the contiguous store and the MFMA-layout load are bank-conflict free.
+//  * select_topk: exact per-row top-k (Eqs. 2, 6, 9) by MSB-first radix select on order-preserving
+//    keys held in registers, ties to the lower index, output in ascending index order.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hisa {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+constexpr int kTileKeys = 32;      // keys per MFMA tile (N of the 32x32x16 MFMA)
+constexpr int kD = 128;            // indexer head dimension of the MFMA path
+constexpr int kTileChunks = 512;   // 16-byte chunks per staged tile: 32 keys x 256 B
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+
+__device__ __forceinline__ float neg_inf() { return -__builtin_inff(); }
+
+union Pack128 {
+  uint4 u;
+  bf16x8 v;
+};
+
+__device__ __forceinline__ bf16x8 as_bf16x8(uint4 u) {
+  Pack128 p;
+  p.u = u;
+  return p.v;
+}
+
+// Orders LDS traffic of one wave: what the wave's lanes stored before is visible to what its
+// lanes load after (LDS serves one wave's requests in issue order; this stops the compiler from
+// reordering across the point).
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ------------------------------------------------------------------------------------------
+// Query fragment: all H = 32*HG heads of one query in MFMA A-operand layout, plus the gates in
+// the accumulator's row layout.  A operand of v_mfma_f32_32x32x16_bf16: lane l supplies row
+// (l % 32) and the 8 contraction elements of half (l / 32); step kk covers d = 16*kk .. 16*kk+15.
+// Accumulator: lane l holds column (l % 32); register i holds row 8*(i/4) + 4*(l/32) + (i%4).
+template <int HG>
+struct QFrag {
+  bf16x8 a[HG][8];
+  float w[HG][16];
+};
+
+template <int HG>
+__device__ __forceinline__ void load_qfrag(QFrag<HG>& f, const uint16_t* __restrict__ q,
+                                           const float* __restrict__ w) {
+  const int lane = lane_id();
+  const int half = lane >> 5;
+  const int r = lane & 31;
+#pragma unroll
+  for (int g = 0; g < HG; ++g) {
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const uint4* p = reinterpret_cast<const uint4*>(q + (g * 32 + r) * kD + kk * 16 + half * 8);
+      f.a[g][kk] = as_bf16x8(*p);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) f.w[g][i] = w[g * 32 + 8 * (i >> 2) + 4 * half + (i & 3)];
+  }
+}
+
+// Score of the 32 keys of a staged tile against every head of the query:
+// sum_j w_j * max(0, q_j . k).  Every lane returns the score of key (lane % 32).
+template <int HG>
+__device__ __forceinline__ float score_tile(const QFrag<HG>& f, const uint4* tile) {
+  const int lane = lane_id();
+  const int half = lane >> 5;
+  const int r = lane & 31;
+  f32x16 acc[HG];
+#pragma unroll
+  for (int g = 0; g < HG; ++g)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[g][i] = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    const int c = 2 * kk + half;
+    const bf16x8 kv = as_bf16x8(tile[r * 16 + (c ^ (r & 15))]);
+#pragma unroll
+    for (int g = 0; g < HG; ++g)
+      acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[g][kk], kv, acc[g], 0, 0, 0);
+  }
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+  for (int g = 0; g < HG; ++g) {
+#pragma unroll
+    for (int i = 0; i < 16; i += 4) {
+      s0 = __builtin_fmaf(__builtin_fmaxf(acc[g][i + 0], 0.f), f.w[g][i + 0], s0);
+      s1 = __builtin_fmaf(__builtin_fmaxf(acc[g][i + 1], 0.f), f.w[g][i + 1], s1);
+      s2 = __builtin_fmaf(__builtin_fmaxf(acc[g][i + 2], 0.f), f.w[g][i + 2], s2);
+      s3 = __builtin_fmaf(__builtin_fmaxf(acc[g][i + 3], 0.f), f.w[g][i + 3], s3);
+    }
+  }
+  float s = (s0 + s1) + (s2 + s3);
+  s += __shfl_xor(s, 32);
+  return s;
+}
+
+// ------------------------------------------------------------------------------------------
+// Tile staging.  Chunk (row r, 16-byte column c) of a tile lives at LDS chunk r*16 + (c ^ (r&15)).
+// A staging step moves chunk position p = i*64 + lane, so consecutive lanes write consecutive
+// 16-byte LDS words and read one 256-byte key row per 16 lanes.
+
+// The chunks a lane holds between fetch and store are kept in ONE vector value (not an array):
+// arrays that live across a barrier end up in scratch memory.
+typedef uint32_t u32x32 __attribute__((ext_vector_type(32)));
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+
+template <class V>
+__device__ __forceinline__ void put4(V& v, int i, uint4 x) {
+  v[4 * i + 0] = x.x;
+  v[4 * i + 1] = x.y;
+  v[4 * i + 2] = x.z;
+  v[4 * i + 3] = x.w;
+}
+
+template <class V>
+__device__ __forceinline__ uint4 get4(const V& v, int i) {
+  return make_uint4(v[4 * i + 0], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]);
+}
+
+// 2-byte (bf16) keys: 8 chunks per lane per tile.
+__device__ __forceinline__ u32x32 tile_fetch_bf16(const uint16_t* __restrict__ base, long row0,
+                                                  long n_rows) {
+  const int lane = lane_id();
+  u32x32 v;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int p = i * 64 + lane;
+    const int r = p >> 4, c = p & 15;
+    long gr = row0 + r;
+    gr = gr < n_rows ? gr : n_rows - 1;
+    put4(v, i, *reinterpret_cast<const uint4*>(base + gr * kD + ((c ^ (r & 15)) << 3)));
+  }
+  return v;
+}
+
+__device__ __forceinline__ void tile_store_bf16(uint4* tile, const u32x32& v) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) tile[i * 64 + lane] = get4(v, i);
+}
+
+// Exact widening of 4 e4m3fn codes (one dword) to 4 bf16 (every e4m3 value is a bf16 value).
+__device__ __forceinline__ uint2 fp8x4_to_bf16x4(uint32_t word) {
+  union {
+    bf16x2 h;
+    uint32_t u;
+  } lo, hi;
+  lo.h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)word, 1.0f, false);
+  hi.h = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8((int)word, 1.0f, true);
+  return make_uint2(lo.u, hi.u);
+}
+
+// 1-byte (fp8) keys: 4 fetches of 16 codes per lane per tile, widened on the way into LDS.
+__device__ __forceinline__ u32x16 tile_fetch_fp8(const uint8_t* __restrict__ base, long row0,
+                                                 long n_rows) {
+  const int lane = lane_id();
+  u32x16 v;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int p = i * 64 + lane;
+    const int r = p >> 3, c8 = p & 7;
+    long gr = row0 + r;
+    gr = gr < n_rows ? gr : n_rows - 1;
+    put4(v, i, *reinterpret_cast<const uint4*>(base + gr * kD + (c8 << 4)));
+  }
+  return v;
+}
+
+__device__ __forceinline__ void tile_store_fp8(uint4* tile, const u32x16& v) {
+  const int lane = lane_id();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int p = i * 64 + lane;
+    const int r = p >> 3, c8 = p & 7;
+    const uint2 a = fp8x4_to_bf16x4(v[4 * i + 0]), b = fp8x4_to_bf16x4(v[4 * i + 1]);
+    const uint2 c = fp8x4_to_bf16x4(v[4 * i + 2]), d = fp8x4_to_bf16x4(v[4 * i + 3]);
+    tile[r * 16 + ((2 * c8) ^ (r & 15))] = make_uint4(a.x, a.y, b.x, b.y);
+    tile[r * 16 + ((2 * c8 + 1) ^ (r & 15))] = make_uint4(c.x, c.y, d.x, d.y);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Order-preserving key of a score: larger score <=> larger key.  -0 counts as +0.  Key 0 is
+// reserved for "not a candidate" (-inf or out of range); real candidates map to >= 1.
+__device__ __forceinline__ uint32_t ordered_key(float s) {
+  if (s == neg_inf()) return 0u;
+  const uint32_t b = __float_as_uint(s + 0.0f);
+  const uint32_t k = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+  return k ? k : 1u;
+}
+
+__device__ __forceinline__ float key_to_score(uint32_t k) {
+  const uint32_t b = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+  return __uint_as_float(b);
+}
+
+__device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                   __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+template <int THREADS, int E>
+struct SelectSmem {
+  static constexpr int NW = THREADS / 64;
+  uint32_t hist[256];
+  uint32_t tab_gt[E * NW];
+  uint32_t tab_eq[E * NW];
+  uint32_t red[3 * NW];
+  uint32_t bcast[2];
+};
+
+// Exact top-k of one row by one workgroup of THREADS threads, n <= THREADS * E elements.
+//   load(i)  -> key of element i (0: not a candidate); element i is held by thread i % THREADS.
+//   emit(pos, i, key): element i is the pos-th selected, in ascending i.
+// Returns the number selected: min(k, #candidates).  Order: key descending, then i ascending.
+// Every thread of the workgroup must call it (it contains workgroup barriers).
+template <int THREADS, int E, class Load, class Emit>
+__device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, int k, Load load,
+                                           Emit emit) {
+  constexpr int NW = THREADS / 64;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+
+  typedef uint32_t keyvec __attribute__((ext_vector_type(E)));
+  keyvec key;   // one vector value, not an array: see the staging note above
+  uint32_t cnt = 0, k_and = 0xffffffffu, k_or = 0u;
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const int i = j * THREADS + tid;
+    const uint32_t kj = (i < n) ? load(i) : 0u;
+    key[j] = kj;
+    if (kj) {
+      ++cnt;
+      k_and &= kj;
+      k_or |= kj;
+    }
+  }
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    cnt += __shfl_xor(cnt, off);
+    k_and &= __shfl_xor(k_and, off);
+    k_or |= __shfl_xor(k_or, off);
+  }
+  if (lane == 0) {
+    sm.red[wave] = cnt;
+    sm.red[NW + wave] = k_and;
+    sm.red[2 * NW + wave] = k_or;
+  }
+  __syncthreads();
+  cnt = 0;
+  k_and = 0xffffffffu;
+  k_or = 0u;
+#pragma unroll
+  for (int v = 0; v < NW; ++v) {
+    cnt += sm.red[v];
+    k_and &= sm.red[NW + v];
+    k_or |= sm.red[2 * NW + v];
+  }
+  const int n_valid = (int)cnt;
+
+  uint32_t tau = 0u;   // threshold key: everything above is selected
+  uint32_t r = 0u;     // how many elements equal to tau are selected (lowest indices first)
+  if (n_valid > k) {
+    const uint32_t diff = k_and ^ k_or;
+    int hi = diff ? 32 - __builtin_clz(diff) : 0;           // low bits that vary among candidates
+    uint32_t pref = (hi >= 32) ? 0u : (k_or >> hi) << hi;   // bits above are common to all
+    uint32_t krem = (uint32_t)k;
+    while (hi > 0) {
+      const int wbits = hi < 8 ? hi : 8;
+      const int shift = hi - wbits;
+      const uint32_t dmask = (1u << wbits) - 1u;
+      for (int b = tid; b < 256; b += THREADS) sm.hist[b] = 0u;
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < E; ++j) {
+        const uint32_t kj = key[j];
+        const bool in = kj && (hi >= 32 || (kj >> hi) == (pref >> hi));
+        if (in) atomicAdd(&sm.hist[(kj >> shift) & dmask], 1u);
+      }
+      __syncthreads();
+      if (wave == 0) {
+        const uint32_t c0 = sm.hist[4 * lane + 0], c1 = sm.hist[4 * lane + 1];
+        const uint32_t c2 = sm.hist[4 * lane + 2], c3 = sm.hist[4 * lane + 3];
+        const uint32_t s = c0 + c1 + c2 + c3;
+        uint32_t S = s;   // inclusive suffix sum over lanes
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          const uint32_t v = __shfl_down(S, off);
+          if (lane + off < 64) S += v;
+        }
+        const uint32_t a3 = S - s, a2 = a3 + c3, a1 = a2 + c2, a0 = a1 + c1;
+        int dsel = -1;
+        uint32_t above = 0;
+        if (a3 < krem && krem <= a3 + c3) { dsel = 3; above = a3; }
+        if (a2 < krem && krem <= a2 + c2) { dsel = 2; above = a2; }
+        if (a1 < krem && krem <= a1 + c1) { dsel = 1; above = a1; }
+        if (a0 < krem && krem <= a0 + c0) { dsel = 0; above = a0; }
+        if (dsel >= 0) {
+          sm.bcast[0] = (uint32_t)(4 * lane + dsel);
+          sm.bcast[1] = krem - above;
+        }
+      }
+      __syncthreads();
+      pref |= sm.bcast[0] << shift;
+      krem = sm.bcast[1];
+      hi = shift;
+    }
+    tau = pref;
+    r = krem;
+  }
+
+  // Ranks in index order.  Element i = j*THREADS + wave*64 + lane, so (j, wave, lane) ascending
+  // is i ascending: count per (j, wave), exclusive-scan the table, add the in-wave rank.
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const uint64_t bg = __ballot(key[j] > tau);
+    const uint64_t be = __ballot(tau != 0u && key[j] == tau);
+    if (lane == 0) {
+      sm.tab_gt[j * NW + wave] = __popcll(bg);
+      sm.tab_eq[j * NW + wave] = __popcll(be);
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    constexpr int NT = E * NW;
+    constexpr int PER = (NT + 63) / 64;
+    uint32_t sg = 0, se = 0;
+#pragma unroll
+    for (int x = 0; x < PER; ++x) {
+      const int e = lane * PER + x;
+      if (e < NT) {
+        sg += sm.tab_gt[e];
+        se += sm.tab_eq[e];
+      }
+    }
+    uint32_t Sg = sg, Se = se;   // inclusive prefix over lanes
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t vg = __shfl_up(Sg, off), ve = __shfl_up(Se, off);
+      if (lane >= off) {
+        Sg += vg;
+        Se += ve;
+      }
+    }
+    uint32_t rg = Sg - sg, re = Se - se;
+#pragma unroll
+    for (int x = 0; x < PER; ++x) {
+      const int e = lane * PER + x;
+      if (e < NT) {
+        const uint32_t tg = sm.tab_gt[e], te = sm.tab_eq[e];
+        sm.tab_gt[e] = rg;
+        sm.tab_eq[e] = re;
+        rg += tg;
+        re += te;
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const bool gt = key[j] > tau;
+    const bool eq = tau != 0u && key[j] == tau;
+    const uint64_t bg = __ballot(gt);
+    const uint64_t be = __ballot(eq);
+    const uint32_t rank_gt = sm.tab_gt[j * NW + wave] + lanes_below(bg);
+    const uint32_t rank_eq = sm.tab_eq[j * NW + wave] + lanes_below(be);
+    if (gt || (eq && rank_eq < r)) {
+      const uint32_t pos = rank_gt + (rank_eq < r ? rank_eq : r);
+      emit((int)pos, j * THREADS + tid, key[j]);
+    }
+  }
+  return n_valid < k ? n_valid : k;
+}
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
+  const uint32_t b = __float_as_uint(x);
+  return (uint16_t)((b + 0x7fffu + ((b >> 16) & 1u)) >> 16);
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) {
+  return __uint_as_float(((uint32_t)h) << 16);
+}
+
+}  // namespace hisa

@@ -1,0 +1,481 @@
+// Kernels of the HISA indexer (gfx950).  Notation follows the paper: B block size, m block
+// budget, k token budget, H indexer heads, d head dimension, q/w/k indexing queries, gates, keys.
+#pragma once
+
+#include <type_traits>
+
+#include "hisa_device.h"
+
+namespace hisa {
+
+enum : int { DT_F32 = 0, DT_BF16 = 1, DT_FP8 = 2 };
+
+// What a scoring kernel needs to know about queries, keys and where scores go.
+struct ScoreArgs {
+  const void* q;             // [T, H, d]
+  const float* w;            // [T, H]
+  const int32_t* q_seq;      // [T] or null
+  const int32_t* q_pos;      // [T] or null
+  int q_pos0;
+  int H, d;
+  const void* keys;          // [n_seq, rows_per_seq, d]: token keys, or pooled keys (pos_div = B)
+  const float* k_scale;      // [n_seq, rows_per_seq] (fp8 token keys) or null
+  const int32_t* seq_len;    // [n_seq]
+  int n_seq;
+  long rows_per_seq;
+  int pos_div;               // 1: rows are tokens; B: rows are blocks (visible rows = pos / B + 1)
+  const int32_t* block_idx;  // [T, m] => gather mode (Eq. 7: candidates = tokens of kept blocks)
+  int m, B;
+  float* out;                // [t_count, ld] scores, row = query - t_begin
+  long ld;
+  int t_begin, t_count;
+  int tiles_per_wave;        // score_ranges: 32-key tiles each wave handles
+};
+
+// Position and sequence of query t, clamped so that no key row past the sequence is visible.
+__device__ __forceinline__ int query_pos(const ScoreArgs& a, int t, int& seq) {
+  int s = a.q_seq ? a.q_seq[t] : 0;
+  s = s < 0 ? 0 : (s >= a.n_seq ? a.n_seq - 1 : s);
+  seq = s;
+  int pos = a.q_pos ? a.q_pos[t] : a.q_pos0 + t;
+  const int sl = a.seq_len[s];
+  return pos < sl ? pos : sl - 1;
+}
+
+__device__ __forceinline__ int visible_rows(const ScoreArgs& a, int pos) {
+  return pos < 0 ? 0 : pos / a.pos_div + 1;
+}
+
+// ------------------------------------------------------------------------------------------
+// Eq. 4: block mean pooling.  One workgroup per (block, sequence).  VEC = elements per 16-byte
+// load (4 fp32 / 8 bf16 / 16 fp8).  Thread (rl, col) sums rows rl, rl+RP, ... of its 16-byte
+// column in fp32; the RP partial rows are then reduced through LDS and divided by the count.
+template <int KDT, int PDT>
+__global__ __launch_bounds__(256) void k_pool(const void* __restrict__ keys,
+                                              const float* __restrict__ k_scale,
+                                              const int32_t* __restrict__ seq_len, long s_max, int d,
+                                              int B, int blk_begin, void* __restrict__ pooled) {
+  constexpr int VEC = KDT == DT_F32 ? 4 : (KDT == DT_BF16 ? 8 : 16);
+  __shared__ float part[256 * VEC];
+  const int seq = blockIdx.y;
+  const int b = blk_begin + blockIdx.x;
+  const int tid = threadIdx.x;
+  const int VC = d / VEC;               // 16-byte columns per key row (<= 256 checked on the host)
+  const int RP = 256 / VC;              // rows in flight per pass
+  const int rl = tid / VC, col = tid % VC;
+  const long M = s_max / B;
+  const int sl = seq_len[seq];
+  long lo = (long)b * B;
+  int nb = (int)((sl - lo) < (long)B ? (sl - lo) : (long)B);
+  if (nb < 0) nb = 0;
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+  if (rl < RP) {
+    const char* base = (const char*)keys + ((long)seq * s_max + lo) * d * (16 / VEC);
+    for (int r = rl; r < nb; r += RP) {
+      const uint4 v = *reinterpret_cast<const uint4*>(base + ((long)r * VC + col) * 16);
+      if (KDT == DT_F32) {
+        acc[0] += __uint_as_float(v.x);
+        acc[1] += __uint_as_float(v.y);
+        acc[2] += __uint_as_float(v.z);
+        acc[3] += __uint_as_float(v.w);
+      } else if (KDT == DT_BF16) {
+        const uint32_t ww[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[2 * e] += __uint_as_float(ww[e] << 16);
+          acc[2 * e + 1] += __uint_as_float(ww[e] & 0xffff0000u);
+        }
+      } else {
+        const float sc = k_scale[(long)seq * s_max + lo + r];
+        const uint32_t ww[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint2 h = fp8x4_to_bf16x4(ww[e]);
+          acc[4 * e + 0] = __builtin_fmaf(sc, __uint_as_float(h.x << 16), acc[4 * e + 0]);
+          acc[4 * e + 1] = __builtin_fmaf(sc, __uint_as_float(h.x & 0xffff0000u), acc[4 * e + 1]);
+          acc[4 * e + 2] = __builtin_fmaf(sc, __uint_as_float(h.y << 16), acc[4 * e + 2]);
+          acc[4 * e + 3] = __builtin_fmaf(sc, __uint_as_float(h.y & 0xffff0000u), acc[4 * e + 3]);
+        }
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) part[rl * d + col * VEC + e] = acc[e];
+  }
+  __syncthreads();
+  for (int i = tid; i < d; i += 256) {
+    float s = 0.f;
+    for (int r = 0; r < RP; ++r) s += part[r * d + i];
+    const float mean = nb > 0 ? s / (float)nb : 0.f;
+    const long o = ((long)seq * M + b) * d + i;
+    if (PDT == DT_F32)
+      ((float*)pooled)[o] = mean;
+    else
+      ((uint16_t*)pooled)[o] = f32_to_bf16_rne(mean);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_fill_f32(float* p, long n, float v) {
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long)gridDim.x * 256) p[i] = v;
+}
+
+// ------------------------------------------------------------------------------------------
+// Eq. 1 / Eq. 5 on the plain fp32 ALU, any H and d (the small fp32 configuration).  One workgroup
+// per (chunk of keys, query); the query's heads and gates sit in LDS, each thread scores one key.
+__global__ __launch_bounds__(256) void k_score_ranges_f32(ScoreArgs a, int keys_per_wg) {
+  extern __shared__ float qs[];   // H*d query values, then H gates
+  const int t = a.t_begin + blockIdx.y;
+  const int tid = threadIdx.x;
+  int seq;
+  const int pos = query_pos(a, t, seq);
+  const int H = a.H, d = a.d;
+  const float* q = (const float*)a.q + (long)t * H * d;
+  for (int i = tid; i < H * d; i += 256) qs[i] = q[i];
+  for (int i = tid; i < H; i += 256) qs[H * d + i] = a.w[(long)t * H + i];
+  __syncthreads();
+  const bool gather = a.block_idx != nullptr;
+  const int n_total = gather ? a.m * a.B : visible_rows(a, pos);
+  const int c0 = blockIdx.x * keys_per_wg;
+  const int c1 = (c0 + keys_per_wg) < n_total ? (c0 + keys_per_wg) : n_total;
+  const float* kbase = (const float*)a.keys + (long)seq * a.rows_per_seq * d;
+  float* out = a.out + (long)blockIdx.y * a.ld;
+  for (int c = c0 + tid; c < c1; c += 256) {
+    long row = c;
+    bool valid = true;
+    if (gather) {
+      const int slot = c / a.B, off = c - slot * a.B;
+      const int blk = a.block_idx[(long)t * a.m + slot];
+      row = (long)blk * a.B + off;
+      valid = blk >= 0 && row <= pos;
+    }
+    float s = neg_inf();
+    if (valid) {
+      const float4* kr = reinterpret_cast<const float4*>(kbase + row * d);
+      s = 0.f;
+      for (int j = 0; j < H; ++j) {
+        const float4* qr = reinterpret_cast<const float4*>(qs + j * d);
+        float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
+        for (int i = 0; i < d / 4; ++i) {
+          const float4 kv = kr[i], qv = qr[i];
+          d0 = __builtin_fmaf(qv.x, kv.x, d0);
+          d1 = __builtin_fmaf(qv.y, kv.y, d1);
+          d2 = __builtin_fmaf(qv.z, kv.z, d2);
+          d3 = __builtin_fmaf(qv.w, kv.w, d3);
+        }
+        const float dot = (d0 + d1) + (d2 + d3);
+        s = __builtin_fmaf(qs[H * d + j], __builtin_fmaxf(dot, 0.f), s);
+      }
+    }
+    out[c] = s;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// One staged tile: fetch (global -> registers), store (registers -> LDS, widening fp8).
+template <int KDT>
+struct TileRegs {
+  typedef typename std::conditional<KDT == DT_BF16, u32x32, u32x16>::type vec_t;
+  vec_t v;
+};
+
+template <int KDT>
+__device__ __forceinline__ void tile_fetch(TileRegs<KDT>& r, const void* base, long row0,
+                                           long n_rows) {
+  if constexpr (KDT == DT_BF16)
+    r.v = tile_fetch_bf16((const uint16_t*)base, row0, n_rows);
+  else
+    r.v = tile_fetch_fp8((const uint8_t*)base, row0, n_rows);
+}
+
+template <int KDT>
+__device__ __forceinline__ void tile_store(uint4* tile, const TileRegs<KDT>& r) {
+  if constexpr (KDT == DT_BF16)
+    tile_store_bf16(tile, r.v);
+  else
+    tile_store_fp8(tile, r.v);
+}
+
+// Where virtual tile v of a query lives: key rows [row0, row0+32), output slots [out0, out0+32).
+// Flat / Stage 1: tile v covers rows 32v ..; gather (Stage 2): tile v is sub-tile v % (B/32) of
+// the kept block in slot v / (B/32).  row0 < 0: the slot is empty (-1 padding).
+struct TileLoc {
+  long row0;
+  long out0;
+};
+
+__device__ __forceinline__ TileLoc tile_loc(const ScoreArgs& a, int t, int v, bool gather) {
+  TileLoc L;
+  if (gather) {
+    const int tpb = a.B >> 5;
+    const int slot = v / tpb, sub = v - slot * tpb;
+    const int blk = a.block_idx[(long)t * a.m + slot];
+    L.out0 = (long)slot * a.B + sub * 32;
+    L.row0 = blk < 0 ? -1 : (long)blk * a.B + sub * 32;
+  } else {
+    L.row0 = (long)v * 32;
+    L.out0 = L.row0;
+  }
+  return L;
+}
+
+// Eq. 1 / Eq. 5 / Eq. 8 on MFMA for arbitrary queries: one workgroup of 4 waves per (group of
+// tiles, query); each wave stages its own tiles (nothing is shared between queries here: this is
+// the decode / two-kernel path).  Writes scores, and -inf for masked slots in gather mode.
+template <int HG, int KDT>
+__global__ __launch_bounds__(256) void k_score_ranges(ScoreArgs a) {
+  __shared__ uint4 stage[4][kTileChunks];
+  const int t = a.t_begin + blockIdx.y;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int seq;
+  const int pos = query_pos(a, t, seq);
+  const bool gather = a.block_idx != nullptr;
+  const int n_vis = gather ? pos + 1 : visible_rows(a, pos);
+  const int n_tiles = gather ? a.m * (a.B >> 5) : (n_vis + 31) >> 5;
+  const int v0 = blockIdx.x * 4 * a.tiles_per_wave;
+  if (v0 >= n_tiles) return;
+  float* out = a.out + (long)blockIdx.y * a.ld;
+  const int rb = KDT == DT_BF16 ? 2 : 1;
+  const char* kbase = (const char*)a.keys + (long)seq * a.rows_per_seq * kD * rb;
+  const float* sbase = a.k_scale ? a.k_scale + (long)seq * a.rows_per_seq : nullptr;
+
+  QFrag<HG> f;
+  load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
+
+  TileRegs<KDT> regs;
+  for (int i = 0; i < a.tiles_per_wave; ++i) {
+    const int v = v0 + wave + 4 * i;
+    if (v >= n_tiles) break;
+    const TileLoc L = tile_loc(a, t, v, gather);
+    float s = neg_inf();
+    if (L.row0 >= 0 && L.row0 < n_vis) {
+      tile_fetch<KDT>(regs, kbase, L.row0, a.rows_per_seq);
+      wave_lds_sync();
+      tile_store<KDT>(stage[wave], regs);
+      wave_lds_sync();
+      s = score_tile<HG>(f, stage[wave]);
+      const long row = L.row0 + (lane & 31);
+      if (KDT == DT_FP8) s *= sbase[row < a.rows_per_seq ? row : a.rows_per_seq - 1];
+      if (row >= n_vis) s = neg_inf();
+    }
+    if (lane < 32 && (gather || L.row0 + lane < n_vis)) out[L.out0 + lane] = s;
+  }
+}
+
+// Eq. 1 / Eq. 5 on MFMA for a causal prefill of ONE sequence with consecutive positions: one
+// workgroup of 8 waves = 8 consecutive queries; 64-key tiles are staged once in LDS (double
+// buffered) and shared by the 8 queries.  Used by the flat DSA indexer and by Stage 1.
+template <int HG, int KDT>
+__global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
+  __shared__ uint4 tiles[2][2][kTileChunks];
+  const int g = gridDim.x - 1 - blockIdx.x;            // longest prefixes first
+  const int th = threadIdx.x, wave = th >> 6, lane = th & 63;
+  const int tl = g * 8 + wave;
+  const bool active = tl < a.t_count;
+  const int t = a.t_begin + (active ? tl : a.t_count - 1);
+  int seq;
+  const int pos = query_pos(a, t, seq);
+  const int n_vis = active ? visible_rows(a, pos) : 0;
+  const int tl_last = (g * 8 + 7) < a.t_count ? (g * 8 + 7) : a.t_count - 1;
+  int seq_last;
+  const int n_max = visible_rows(a, query_pos(a, a.t_begin + tl_last, seq_last));
+  const int n_iter = (n_max + 63) >> 6;
+  float* out = a.out + (long)(active ? tl : 0) * a.ld;
+  const char* kbase = (const char*)a.keys;
+  const float* sbase = a.k_scale;
+
+  QFrag<HG> f;
+  load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
+
+  // cooperative staging of a 64-key tile: bf16 1024 chunks (2 per thread), fp8 512 fetches (1)
+  constexpr int NF = KDT == DT_BF16 ? 2 : 1;
+  typedef uint32_t prevec __attribute__((ext_vector_type(4 * NF)));
+  prevec pre;
+  auto fetch = [&](int it) {
+#pragma unroll
+    for (int i = 0; i < NF; ++i) {
+      const int p = i * 512 + th;
+      long gr;
+      if (KDT == DT_BF16) {
+        const int sub = p >> 9, pp = p & 511, r = pp >> 4, c = pp & 15;
+        gr = (long)it * 64 + sub * 32 + r;
+        gr = gr < a.rows_per_seq ? gr : a.rows_per_seq - 1;
+        put4(pre, i, *reinterpret_cast<const uint4*>(kbase + (gr * kD + ((c ^ (r & 15)) << 3)) * 2));
+      } else {
+        const int sub = p >> 8, pp = p & 255, r = pp >> 3, c8 = pp & 7;
+        gr = (long)it * 64 + sub * 32 + r;
+        gr = gr < a.rows_per_seq ? gr : a.rows_per_seq - 1;
+        put4(pre, i, *reinterpret_cast<const uint4*>(kbase + gr * kD + (c8 << 4)));
+      }
+    }
+  };
+  auto store = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < NF; ++i) {
+      const int p = i * 512 + th;
+      if (KDT == DT_BF16) {
+        tiles[buf][p >> 9][p & 511] = get4(pre, i);
+      } else {
+        const int sub = p >> 8, pp = p & 255, r = pp >> 3, c8 = pp & 7;
+        const uint2 x = fp8x4_to_bf16x4(pre[4 * i + 0]), y = fp8x4_to_bf16x4(pre[4 * i + 1]);
+        const uint2 z = fp8x4_to_bf16x4(pre[4 * i + 2]), u = fp8x4_to_bf16x4(pre[4 * i + 3]);
+        tiles[buf][sub][r * 16 + ((2 * c8) ^ (r & 15))] = make_uint4(x.x, x.y, y.x, y.y);
+        tiles[buf][sub][r * 16 + ((2 * c8 + 1) ^ (r & 15))] = make_uint4(z.x, z.y, u.x, u.y);
+      }
+    }
+  };
+
+  if (n_iter > 0) {
+    fetch(0);
+    store(0);
+  }
+  __syncthreads();
+  int cur = 0;
+  for (int it = 0; it < n_iter; ++it) {
+    if (it + 1 < n_iter) fetch(it + 1);
+#pragma unroll
+    for (int sub = 0; sub < 2; ++sub) {
+      const int s0 = it * 64 + sub * 32;
+      if (s0 < n_vis) {
+        float s = score_tile<HG>(f, tiles[cur][sub]);
+        const int row = s0 + (lane & 31);
+        if (KDT == DT_FP8) s *= sbase[row < a.rows_per_seq ? row : (int)a.rows_per_seq - 1];
+        if (lane < 32 && row < n_vis) out[row] = s;
+      }
+    }
+    if (it + 1 < n_iter) store(cur ^ 1);
+    __syncthreads();
+    cur ^= 1;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Row-wise exact top-k over scores in global memory (Eqs. 2, 6, 9).
+enum : int { MAP_FLAT = 0, MAP_BLOCKS = 1, MAP_CAND = 2, MAP_PAIRS = 3 };
+
+struct SelectArgs {
+  const float* scores;       // [rows, ld]
+  long ld;
+  const int32_t* idx_in;     // MAP_PAIRS: [rows, ld] ids aligned with scores
+  const int32_t* q_seq;      // position info of the queries (FLAT / BLOCKS)
+  const int32_t* q_pos;
+  const int32_t* seq_len;
+  int q_pos0, n_seq, pos_div;
+  int t_begin;               // global query index of row 0
+  int n_fixed;               // CAND / PAIRS: elements per row
+  const int32_t* block_idx;  // MAP_CAND: [T, m] (global query indexing)
+  int m, B;
+  int seg_len, n_seg;        // FLAT: the row is cut into n_seg segments of seg_len (grid.x)
+  int k;
+  int32_t* out_idx;          // [rows * n_seg, k]
+  float* out_scores;         // same shape, or null
+};
+
+template <int THREADS, int E, int MAP>
+__global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
+  __shared__ SelectSmem<THREADS, E> sm;
+  const int row = blockIdx.y, seg = blockIdx.x;
+  const int t = a.t_begin + row;
+  const float* sc = a.scores + (long)row * a.ld;
+  int n = a.n_fixed;
+  int base = 0;
+  if (MAP == MAP_FLAT || MAP == MAP_BLOCKS) {
+    int s = a.q_seq ? a.q_seq[t] : 0;
+    s = s < 0 ? 0 : (s >= a.n_seq ? a.n_seq - 1 : s);
+    int pos = a.q_pos ? a.q_pos[t] : a.q_pos0 + t;
+    const int sl = a.seq_len[s];
+    pos = pos < sl ? pos : sl - 1;
+    const int n_vis = pos < 0 ? 0 : pos / a.pos_div + 1;
+    base = seg * a.seg_len;
+    n = n_vis - base;
+    n = n < 0 ? 0 : (n > a.seg_len ? a.seg_len : n);
+  }
+  const long orow = (long)row * a.n_seg + seg;
+  int32_t* oi = a.out_idx + orow * a.k;
+  float* os = a.out_scores ? a.out_scores + orow * a.k : nullptr;
+  const int n_last = n - 1;
+  auto load = [&](int i) -> uint32_t {
+    if (MAP == MAP_BLOCKS && (i == 0 || i == n_last)) return 0xffffffffu;   // forced blocks
+    return ordered_key(sc[base + i]);
+  };
+  auto emit = [&](int p, int i, uint32_t key) {
+    int id;
+    if (MAP == MAP_CAND) {
+      const int slot = i / a.B;
+      id = a.block_idx[(long)t * a.m + slot] * a.B + (i - slot * a.B);
+    } else if (MAP == MAP_PAIRS) {
+      id = a.idx_in[(long)row * a.ld + i];
+    } else {
+      id = base + i;
+    }
+    oi[p] = id;
+    if (os) os[p] = key_to_score(key);
+  };
+  const int n_out = select_topk<THREADS, E>(sm, n, a.k, load, emit);
+  for (int p = n_out + threadIdx.x; p < a.k; p += THREADS) {
+    oi[p] = -1;
+    if (os) os[p] = neg_inf();
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Stage 2 fused (Eqs. 7-9): one workgroup of 4 waves per query scores every tile of the kept
+// blocks into LDS and selects the top k there; only the k indices leave the CU.
+template <int HG, int KDT, int E>
+__global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int32_t* topk_idx,
+                                                         float* topk_scores) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint4* stage = reinterpret_cast<uint4*>(smem);                       // 4 x 8 KB
+  float* sc = reinterpret_cast<float*>(smem + 4 * kTileChunks * 16);   // m*B scores
+  const int n_slots = a.m * a.B;
+  SelectSmem<256, E>& sm =
+      *reinterpret_cast<SelectSmem<256, E>*>(smem + 4 * kTileChunks * 16 + (size_t)n_slots * 4);
+  const int t = a.t_begin + (gridDim.x - 1 - blockIdx.x);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  int seq;
+  const int pos = query_pos(a, t, seq);
+  const int n_vis = pos + 1;
+  const int n_tiles = n_slots >> 5;
+  const int rb = KDT == DT_BF16 ? 2 : 1;
+  const char* kbase = (const char*)a.keys + (long)seq * a.rows_per_seq * kD * rb;
+  const float* sbase = a.k_scale ? a.k_scale + (long)seq * a.rows_per_seq : nullptr;
+
+  QFrag<HG> f;
+  load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
+
+  uint4* my = stage + wave * kTileChunks;
+  TileRegs<KDT> regs;
+  for (int v = wave; v < n_tiles; v += 4) {
+    const TileLoc L = tile_loc(a, t, v, true);
+    float s = neg_inf();
+    if (L.row0 >= 0 && L.row0 < n_vis) {
+      tile_fetch<KDT>(regs, kbase, L.row0, a.rows_per_seq);
+      wave_lds_sync();
+      tile_store<KDT>(my, regs);
+      wave_lds_sync();
+      s = score_tile<HG>(f, my);
+      const long row = L.row0 + (lane & 31);
+      if (KDT == DT_FP8) s *= sbase[row < a.rows_per_seq ? row : a.rows_per_seq - 1];
+      if (row >= n_vis) s = neg_inf();
+    }
+    if (lane < 32) sc[L.out0 + lane] = s;
+  }
+  __syncthreads();
+
+  int32_t* oi = topk_idx + (long)t * k;
+  float* os = topk_scores ? topk_scores + (long)t * k : nullptr;
+  auto load = [&](int i) -> uint32_t { return ordered_key(sc[i]); };
+  auto emit = [&](int p, int i, uint32_t key) {
+    const int slot = i / a.B;
+    oi[p] = a.block_idx[(long)t * a.m + slot] * a.B + (i - slot * a.B);
+    if (os) os[p] = key_to_score(key);
+  };
+  const int n_out = select_topk<256, E>(sm, n_slots, k, load, emit);
+  for (int p = n_out + threadIdx.x; p < k; p += 256) {
+    oi[p] = -1;
+    if (os) os[p] = neg_inf();
+  }
+}
+
+}  // namespace hisa

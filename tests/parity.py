@@ -1,0 +1,164 @@
+"""GPU-vs-oracle comparison of every call of the library on one workload.
+
+The HIP path and the oracle get the same stored bits.  Stage by stage:
+  pool      pooled keys vs block means (Eq. 4) within rtol of the block's largest component;
+  Stage 1   block scores (Eq. 5) within rtol, block sets (Eq. 6) by the threshold rule, computed by
+            the oracle from the GPU's own pooled bits;
+  Stage 2   candidate scores (Eq. 8) within rtol and token sets (Eq. 9) by the threshold rule,
+            computed by the oracle from the GPU's own block_idx; both the two-kernel and the fused
+            path when the shapes allow;
+  flat      Eqs. 1-2 by the threshold rule.
+Sets are compared as sets; the GPU's rows must be ascending with -1 padding at the end.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import hisa_oracle as O
+from paper_2603_28458_amd import hisa
+from tests.util import check_scores, check_set, oracle_args, rtol_for
+
+
+def _np(t):
+    if t is None:
+        return None
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def sample_queries(wl, n, seed=0):
+    """Stratified sample: uniform over the queries plus the regime boundaries of Section 4.1
+    (pos+1 in {k, k+1, mB, mB+1}), block edges, the first and last query and the needle targets."""
+    rng = np.random.default_rng(seed)
+    pos = wl.positions()
+    pick = set(rng.choice(wl.T, size=min(n, wl.T), replace=False).tolist())
+    pick |= {0, wl.T - 1}
+    for p in (wl.k - 1, wl.k, wl.m * wl.B - 1, wl.m * wl.B, wl.B - 1, wl.B, 2 * wl.B - 1):
+        hit = np.nonzero(pos == p)[0]
+        if hit.size:
+            pick.add(int(hit[0]))
+    for (_, _, t_star, _) in wl.needles:
+        pick.add(int(t_star))
+    return np.array(sorted(pick), dtype=np.int64)
+
+
+def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False):
+    """Runs the four entry points on `wl` and checks them on `queries` (all if None).
+    Returns a dict of statistics (max relative score error, number of threshold swaps)."""
+    rtol = rtol_for(wl)
+    Q, K = hisa.to_device(wl)
+    pd_code = hisa.DTYPE_CODE[wl.pooled_dtype]
+    qs = np.arange(wl.T) if queries is None else np.asarray(queries)
+    pos = wl.positions()
+    stats = {}
+
+    # ---- pool (Eq. 4)
+    pooled_gpu = hisa.hisa_pool_blocks(K, wl.B, pooled_dtype=pd_code)
+    torch.cuda.synchronize()
+    pooled_bits = _np(pooled_gpu)
+    want = O.pool_blocks(wl.keys, wl.k_dtype, wl.k_scale, wl.seq_len, wl.B, wl.pooled_dtype)
+    g = O.decode(pooled_bits, wl.pooled_dtype).reshape(-1, wl.d)
+    w_ = O.decode(want, wl.pooled_dtype).reshape(-1, wl.d)
+    stats["pool_err"] = check_scores(g, w_, rtol, "pooled keys")
+
+    # ---- Stage 1 (Eqs. 5-6) on the GPU's pooled bits
+    block_idx, J = hisa.hisa_block_score_topk(Q, K, pooled_gpu, pd_code, wl.B, wl.m, want_scores=True)
+    block_idx2, _ = hisa.hisa_block_score_topk(Q, K, pooled_gpu, pd_code, wl.B, wl.m)   # workspace path
+    torch.cuda.synchronize()
+    assert torch.equal(block_idx, block_idx2), "Stage 1 differs between score-output and workspace paths"
+    bi = _np(block_idx)
+    o_bi, o_J = O.hisa_block_score_topk(**oracle_args(wl, keys=False), pooled=pooled_bits,
+                                        pooled_dtype=wl.pooled_dtype, B=wl.B, m=wl.m, queries=qs)
+    stats["J_err"] = check_scores(_np(J)[qs], o_J, rtol, "block scores")
+    swaps = 0
+    for i, t in enumerate(qs):
+        b_t = int(pos[t]) // wl.B
+        row = bi[t]
+        v = row[row >= 0]
+        assert v.size == min(wl.m, b_t + 1), (t, v.size)
+        assert v[0] == 0 and v[-1] == b_t, f"query {t}: forced blocks missing"
+        assert np.all(row[v.size:] == -1) and np.all(np.diff(v) > 0)
+        if b_t + 1 > wl.m:
+            # the forced blocks 0 and b_t never take part in a swap: compare the free slots
+            ov = o_bi[i][o_bi[i] >= 0]
+            swaps += check_set(v[1:-1], ov[1:-1], np.arange(1, b_t), o_J[i, 1:b_t], rtol,
+                               f"block set of query {t}")
+        else:
+            assert np.array_equal(v, np.arange(b_t + 1))
+            assert np.all(row[v.size:] == -1)
+    stats["block_swaps"] = swaps
+
+    # ---- Stage 2 (Eqs. 7-9) on the GPU's block_idx: two-kernel path with candidate scores
+    topk_idx, topk_sc, cand = hisa.hisa_token_refine_topk(Q, K, wl.B, wl.m, block_idx, wl.k,
+                                                          want_topk_scores=True, want_cand_scores=True)
+    torch.cuda.synchronize()
+    o_ti, o_ts, o_cand = O.hisa_token_refine_topk(**oracle_args(wl), B=wl.B, m=wl.m, block_idx=bi[qs],
+                                                  k=wl.k, queries=qs)
+    stats["cand_err"] = check_scores(_np(cand)[qs], o_cand, rtol, "candidate scores")
+    ti = _np(topk_idx)
+    ts = _np(topk_sc)
+    stats["token_swaps"] = _check_token_sets(wl, qs, bi, ti, ts, o_ti, o_cand, rtol, "two-kernel")
+
+    # ---- Stage 2 fused path (taken by the library when cand_scores is not requested)
+    if fused is None:
+        fused = wl.q_dtype == "bf16" and wl.T >= 256 and wl.m * wl.B <= 16384
+    if fused:
+        f_idx, f_sc, _ = hisa.hisa_token_refine_topk(Q, K, wl.B, wl.m, block_idx, wl.k, want_topk_scores=True)
+        f_idx2, _, _ = hisa.hisa_token_refine_topk(Q, K, wl.B, wl.m, block_idx, wl.k)
+        torch.cuda.synchronize()
+        assert torch.equal(f_idx, f_idx2)
+        stats["fused_swaps"] = _check_token_sets(wl, qs, bi, _np(f_idx), _np(f_sc), o_ti, o_cand, rtol, "fused")
+        # same fp32 scores, same rule: the two GPU paths must agree exactly
+        assert torch.equal(f_idx, topk_idx), "fused and two-kernel Stage 2 select different sets"
+    else:
+        n_idx, _, _ = hisa.hisa_token_refine_topk(Q, K, wl.B, wl.m, block_idx, wl.k)
+        torch.cuda.synchronize()
+        assert torch.equal(n_idx, topk_idx)
+
+    # ---- end to end: where the GPU's block set equals the oracle's own, the token set follows it
+    o_full = O.hisa_indexer(**oracle_args(wl), seq_len=wl.seq_len, B=wl.B, m=wl.m, k=wl.k,
+                            pooled_dtype=wl.pooled_dtype, queries=qs, pooled=want)
+    same = [i for i in range(qs.size) if np.array_equal(o_full["block_idx"][i], bi[qs[i]])]
+    stats["same_block_sets"] = len(same) / max(1, qs.size)
+    for i in same:
+        toks = O.candidate_tokens(bi[qs[i]][bi[qs[i]] >= 0].astype(np.int64), int(pos[qs[i]]), wl.B)
+        check_set(ti[qs[i]], o_full["topk_idx"][i], toks, o_full["cand_scores"][i, :toks.size], rtol,
+                  f"end-to-end set of query {qs[i]}")
+
+    # ---- flat DSA (Eqs. 1-2)
+    if check_flat:
+        fl_idx, fl_sc = hisa.dsa_flat_indexer_topk(Q, K, wl.k, want_topk_scores=True)
+        torch.cuda.synchronize()
+        fi, fs = _np(fl_idx), _np(fl_sc)
+        o_fi, o_fs, rows = O.dsa_flat_indexer_topk(**oracle_args(wl), k=wl.k, queries=qs, return_scores=True)
+        swaps = 0
+        for i, t in enumerate(qs):
+            ids = np.arange(rows[i].size)
+            swaps += check_set(fi[t], o_fi[i], ids, rows[i], rtol, f"flat set of query {t}")
+            nv = int((fi[t] >= 0).sum())
+            check_scores(fs[t, :nv][None], rows[i][fi[t, :nv]][None], rtol, f"flat scores of query {t}")
+            assert np.all(np.isneginf(fs[t, nv:]))
+        stats["flat_swaps"] = swaps
+        stats["iou_hisa_flat"] = float(np.mean([O.iou(ti[t], fi[t]) for t in qs]))
+    if verbose:
+        print(wl.name, stats, flush=True)
+    return stats
+
+
+def _check_token_sets(wl, qs, bi, ti, ts, o_ti, o_cand, rtol, what):
+    pos = wl.positions()
+    swaps = 0
+    for i, t in enumerate(qs):
+        C = bi[t][bi[t] >= 0].astype(np.int64)
+        toks = O.candidate_tokens(C, int(pos[t]), wl.B)
+        sc = o_cand[i, :toks.size]
+        swaps += check_set(ti[t], o_ti[i], toks, sc, rtol, f"{what} token set of query {t}")
+        nv = int((ti[t] >= 0).sum())
+        assert nv == min(wl.k, toks.size)
+        if ts is not None:
+            want = sc[np.searchsorted(toks, ti[t, :nv])]
+            check_scores(ts[t, :nv][None], want[None], rtol, f"{what} top-k scores of query {t}")
+            assert np.all(np.isneginf(ts[t, nv:]))
+    return swaps

@@ -1,0 +1,93 @@
+"""The C ABI without a GPU: the library loads, exports every declared symbol, and rejects bad
+arguments on the host before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2603_28458_amd import hisa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(hisa.LIB_PATH):
+        from paper_2603_28458_amd.build import build
+        build(verbose=False)
+    return hisa.lib()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "hisa.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b((?:hisa|dsa)_[a-z_]+)\s*\(", header))
+    assert declared == set(hisa.EXPORTS), declared ^ set(hisa.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings_and_version(lib):
+    assert hisa.status_string(0) == "ok"
+    assert "m*B >= k" in hisa.status_string(4)
+    assert hisa.version().count(".") == 1
+
+
+def _structs(T=512, H=64, d=128, n_seq=1, s_max=1024, qd=hisa.HISA_BF16, kd=hisa.HISA_BF16, fake=0x1000):
+    q = hisa._Queries(fake, fake, None, None, T, H, 0, qd)
+    k = hisa._Keys(fake, fake, fake, n_seq, s_max, d, kd)
+    return q, k
+
+
+def test_host_side_validation_rejects_before_launch(lib):
+    """Pointers here are fake non-null values: every call must fail in validation, never launch."""
+    fake = 0x1000
+    q, k = _structs()
+    i32 = C.c_int32
+    # infeasible budgets (Section 4.1: m*B >= k), m < 2
+    assert lib.hisa_token_refine_topk(C.byref(q), C.byref(k), 128, 4, fake, 2048, fake, None, None, None, 0, None) == 4
+    assert lib.hisa_block_score_topk(C.byref(q), C.byref(k), fake, 1, 128, 1, fake, None, fake, 1 << 30, None) == 4
+    # null pointers
+    assert lib.hisa_token_refine_topk(C.byref(q), C.byref(k), 128, 8, None, 512, fake, None, None, None, 0, None) == 1
+    assert lib.hisa_pool_blocks(C.byref(k), 128, 0, 8, None, 1, None) == 1
+    assert lib.dsa_flat_indexer_topk(None, C.byref(k), 64, fake, None, fake, 1 << 30, None) == 1
+    # shapes: s_max not a multiple of B, unsupported H / d on the MFMA path, block range
+    assert lib.hisa_pool_blocks(C.byref(k), 100, 0, 8, fake, 1, None) == 2
+    assert lib.hisa_pool_blocks(C.byref(k), 128, 0, 9, fake, 1, None) == 2
+    q2, k2 = _structs(H=48)
+    assert lib.dsa_flat_indexer_topk(C.byref(q2), C.byref(k2), 64, fake, None, fake, 1 << 30, None) == 2
+    q2, k2 = _structs(d=64)
+    assert lib.dsa_flat_indexer_topk(C.byref(q2), C.byref(k2), 64, fake, None, fake, 1 << 30, None) == 2
+    assert lib.hisa_token_refine_topk(C.byref(q), C.byref(k), 48, 16, fake, 512, fake, None, None, None, 0, None) == 2
+    # dtype combinations
+    q2, k2 = _structs(qd=hisa.HISA_F32, kd=hisa.HISA_BF16)
+    assert lib.dsa_flat_indexer_topk(C.byref(q2), C.byref(k2), 64, fake, None, fake, 1 << 30, None) == 3
+    assert lib.hisa_pool_blocks(C.byref(k), 128, 0, 8, fake, 2, None) == 3
+    # workspace missing / too small
+    assert lib.dsa_flat_indexer_topk(C.byref(q), C.byref(k), 64, fake, None, None, 0, None) == 5
+    assert lib.dsa_flat_indexer_topk(C.byref(q), C.byref(k), 64, fake, None, fake, 100, None) == 5
+    assert lib.hisa_block_score_topk(C.byref(q), C.byref(k), fake, 1, 128, 4, fake, None, None, 0, None) == 5
+    qs, ks = _structs(T=8)
+    assert lib.hisa_token_refine_topk(C.byref(qs), C.byref(ks), 128, 8, fake, 512, fake, None, None, None, 0, None) == 5
+    # alignment
+    q3 = hisa._Queries(fake + 4, fake, None, None, 512, 64, 0, hisa.HISA_BF16)
+    assert lib.dsa_flat_indexer_topk(C.byref(q3), C.byref(k), 64, fake, None, fake, 1 << 30, None) == 6
+
+
+def test_workspace_sizes(lib):
+    q, k = _structs(T=65536, s_max=65536)
+    assert lib.hisa_workspace_bytes(hisa.OP_POOL, C.byref(q), C.byref(k), 128, 64, 2048, 0) == 0
+    assert lib.hisa_workspace_bytes(hisa.OP_BLOCK_SCORE_TOPK, C.byref(q), C.byref(k), 128, 64, 2048, 0) == 65536 * 512 * 4
+    assert lib.hisa_workspace_bytes(hisa.OP_TOKEN_REFINE_TOPK, C.byref(q), C.byref(k), 128, 64, 2048, 0) == 0
+    q2, k2 = _structs(T=32, s_max=131072, n_seq=32)
+    assert lib.hisa_workspace_bytes(hisa.OP_TOKEN_REFINE_TOPK, C.byref(q2), C.byref(k2), 128, 64, 2048, 0) == 32 * 8192 * 4
+    flat = lib.hisa_workspace_bytes(hisa.OP_FLAT_TOPK, C.byref(q), C.byref(k), 1, 0, 2048, 0)
+    assert 8 * 65536 * 4 <= flat <= (4 << 30) + 4096
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(hisa, "_lib", None)
+    monkeypatch.setattr(hisa, "LIB_PATH", "/nonexistent/libhisa.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        hisa.lib()

@@ -1,0 +1,119 @@
+"""Parity of the HIP library against the CPU oracle, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_28458_amd import workloads as W
+from tests.parity import run_and_check, sample_queries
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(wl, **kw):
+    print(f"\n[parity] {wl.name}: T={wl.T} H={wl.H} d={wl.d} B={wl.B} m={wl.m} k={wl.k} "
+          f"q={wl.q_dtype} k={wl.k_dtype} n_seq={wl.n_seq} s_max={wl.s_max} seed={wl.seed}", flush=True)
+    st = run_and_check(wl, verbose=True, **kw)
+    return st
+
+
+def test_tiny_fp32_config_all_queries():
+    st = _run(W.config("tiny_f32"))
+    assert st["block_swaps"] == 0 and st["token_swaps"] == 0 and st["flat_swaps"] == 0
+
+
+@pytest.mark.parametrize("k_dtype", ["bf16", "fp8_e4m3"])
+def test_small_prefill_ragged_tail(k_dtype):
+    # 1467 tokens: 11 full blocks of 128 and a ragged one of 59; several 64-key tiles per query
+    wl = W.make_workload(f"small_{k_dtype}", seq_len=1467, T=1467, H=64, d=128, B=128, m=4, k=256,
+                         q_dtype="bf16", k_dtype=k_dtype, n_needles=4, seed=101)
+    _run(wl)
+
+
+@pytest.mark.parametrize("B,m,k", [(32, 8, 128), (64, 6, 200), (256, 3, 512)])
+def test_block_sizes(B, m, k):
+    wl = W.make_workload(f"B{B}", seq_len=2100, T=2100, H=64, d=128, B=B, m=m, k=k, q_dtype="bf16",
+                         k_dtype="bf16", seed=102 + B)
+    _run(wl, queries=sample_queries(wl, 200))
+
+
+def test_32_heads_and_fp8():
+    wl = W.make_workload("H32", seq_len=900, T=900, H=32, d=128, B=128, m=3, k=300, q_dtype="bf16",
+                         k_dtype="fp8_e4m3", seed=103)
+    _run(wl, queries=sample_queries(wl, 150))
+
+
+def test_chunk_against_longer_prefix():
+    # 300 queries at the end of a 5000-token prefix (q_pos0 > 0); two-kernel and fused Stage 2
+    wl = W.make_workload("chunk", seq_len=5000, T=300, H=64, d=128, B=128, m=8, k=512, q_dtype="bf16",
+                         k_dtype="bf16", n_needles=3, seed=104)
+    _run(wl)
+
+
+@pytest.mark.parametrize("k_dtype", ["bf16", "fp8_e4m3"])
+def test_decode_batch_ragged_lengths(k_dtype):
+    wl = W.make_workload(f"decode_{k_dtype}", n_seq=5, seq_len=[4000, 3333, 129, 128, 1], T=5, H=64, d=128,
+                         B=128, m=6, k=512, q_dtype="bf16", k_dtype=k_dtype, mode="decode", seed=105)
+    _run(wl)
+
+
+def test_fp32_generic_shapes():
+    wl = W.make_workload("f32_odd", seq_len=777, T=777, H=3, d=20, B=16, m=5, k=50, q_dtype="f32", k_dtype="f32",
+                         seed=106)
+    _run(wl, queries=sample_queries(wl, 200))
+    wl = W.make_workload("f32_dec", n_seq=3, seq_len=[300, 17, 64], T=3, H=8, d=64, B=32, m=4, k=100, q_dtype="f32",
+                         k_dtype="f32", mode="decode", seed=107)
+    _run(wl)
+
+
+def test_degenerate_inputs():
+    # one token; k larger than every prefix; m covering everything (HISA == flat, Section 4.1)
+    wl = W.make_workload("one", seq_len=1, T=1, H=64, d=128, B=128, m=2, k=256, q_dtype="bf16", k_dtype="bf16",
+                         seed=108)
+    _run(wl)
+    wl = W.make_workload("allsel", seq_len=500, T=500, H=64, d=128, B=128, m=4, k=512, q_dtype="bf16",
+                         k_dtype="bf16", seed=109)
+    st = _run(wl)
+    wl = W.make_workload("mcovers", seq_len=1024, T=1024, H=64, d=128, B=128, m=8, k=128, q_dtype="bf16",
+                         k_dtype="bf16", seed=110)
+    st = _run(wl)
+    assert st["iou_hisa_flat"] == 1.0
+
+
+def test_ties_and_zero_scores():
+    # every dot product negative -> every score exactly 0 -> the lowest indices win everywhere
+    wl = W.make_workload("zeros", seq_len=1500, T=1500, H=64, d=128, B=128, m=4, k=300, q_dtype="bf16",
+                         k_dtype="bf16", seed=111)
+    q = np.abs(W._bf16_bits_to_f32(wl.q))
+    wl.q = W._to_bf16_bits(q)
+    wl.keys = W._to_bf16_bits(-np.abs(W._bf16_bits_to_f32(wl.keys)))
+    st = _run(wl, queries=sample_queries(wl, 100))
+    assert st["token_swaps"] == 0 and st["flat_swaps"] == 0 and st["block_swaps"] == 0
+    # duplicated keys: exact ties between distinct tokens
+    wl = W.make_workload("dups", seq_len=1024, T=1024, H=64, d=128, B=128, m=4, k=200, q_dtype="bf16",
+                         k_dtype="bf16", seed=112)
+    wl.keys[0, 1::2] = wl.keys[0, 0::2]
+    _run(wl, queries=sample_queries(wl, 100))
+
+
+def test_negative_gates():
+    wl = W.make_workload("negw", seq_len=1300, T=1300, H=64, d=128, B=128, m=5, k=256, q_dtype="bf16",
+                         k_dtype="bf16", seed=113)
+    wl.w = (wl.w - np.float32(0.5)).astype(np.float32)
+    _run(wl, queries=sample_queries(wl, 150))
+
+
+def test_run_to_run_determinism():
+    from paper_2603_28458_amd import hisa
+    wl = W.make_workload("det", seq_len=3000, T=3000, H=64, d=128, B=128, m=8, k=512, q_dtype="bf16",
+                         k_dtype="bf16", seed=114)
+    Q, K = hisa.to_device(wl)
+    outs = []
+    for _ in range(2):
+        pooled = hisa.hisa_pool_blocks(K, wl.B)
+        bi, _ = hisa.hisa_block_score_topk(Q, K, pooled, hisa.HISA_BF16, wl.B, wl.m)
+        ti, _, _ = hisa.hisa_token_refine_topk(Q, K, wl.B, wl.m, bi, wl.k)
+        fi, _ = hisa.dsa_flat_indexer_topk(Q, K, wl.k)
+        torch.cuda.synchronize()
+        outs.append((pooled.clone(), bi.clone(), ti.clone(), fi.clone()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)

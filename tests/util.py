@@ -47,31 +47,33 @@ def check_scores(got, want, rtol, what=""):
     return float((err / np.maximum(A, 1e-300)).max())
 
 
-def check_set(got_ids, want_ids, id_scores, rtol, what="", universe=None):
+def check_set(got_ids, want_ids, cand_ids, cand_scores, rtol, what=""):
     """The selection rule of the benchmark definition: the two index sets have the same size and
     every id in their symmetric difference has an oracle score within rtol * max(|tau|, A) of the
-    oracle's threshold tau (its worst selected score).  id_scores: dict-like id -> oracle score
-    for every candidate; A = max |score| over the candidates.  Also checks uniqueness and that
-    every got id is a candidate."""
-    g = np.asarray(got_ids)
-    g = g[g >= 0]
+    oracle's threshold tau (its worst selected score); A = max |score| over the candidates.
+    cand_ids / cand_scores: every candidate id with its oracle score.  Also checked: ids unique,
+    ascending, -1 padding at the end only, every id a candidate.  Returns the number of swaps."""
+    got_ids = np.asarray(got_ids)
+    n_valid = int((got_ids >= 0).sum())
+    g = got_ids[:n_valid]
+    assert np.all(got_ids[n_valid:] == -1) and np.all(g >= 0), f"{what}: padding is not a suffix of -1"
+    assert np.all(np.diff(g) > 0), f"{what}: ids not strictly ascending"
     wv = np.asarray(want_ids)
     wv = wv[wv >= 0]
-    assert len(set(g.tolist())) == g.size, f"{what}: duplicate ids"
     assert g.size == wv.size, f"{what}: {g.size} valid ids, oracle has {wv.size}"
-    sg, sw = set(g.tolist()), set(wv.tolist())
-    if universe is not None:
-        assert sg <= universe, f"{what}: ids outside the candidate set: {sorted(sg - universe)[:8]}"
-    if sg == sw:
+    cand_ids = np.asarray(cand_ids)
+    cand_scores = np.asarray(cand_scores, dtype=np.float64)
+    assert np.all(np.isin(g, cand_ids)), f"{what}: ids outside the candidate set"
+    diff = np.setxor1d(g, wv)
+    if diff.size == 0:
         return 0
-    diff = sg ^ sw
-    sc = id_scores
-    allv = np.array([sc[i] for i in (universe if universe is not None else sw | sg)])
-    A = np.abs(allv).max()
-    tau = min(sc[i] for i in sw)
+    order = np.argsort(cand_ids)
+    sid, ssc = cand_ids[order], cand_scores[order]
+    sc_diff = ssc[np.searchsorted(sid, diff)]
+    tau = ssc[np.searchsorted(sid, wv)].min()
+    A = np.abs(cand_scores).max()
     tol = rtol * max(abs(tau), A)
-    for i in diff:
-        assert i in sc, f"{what}: id {i} is not a candidate"
-        assert abs(sc[i] - tau) <= tol, (f"{what}: id {i} score {sc[i]!r} differs from threshold "
-                                         f"{tau!r} by more than {tol:.3g}")
-    return len(diff)
+    worst = np.abs(sc_diff - tau).max()
+    assert worst <= tol, (f"{what}: {diff.size} ids differ from the oracle's set and one lies "
+                          f"{worst:.3g} from the threshold {tau:.6g} (allowed {tol:.3g})")
+    return int(diff.size // 2)
