@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the HISA indexer hot path on one MI355X.
+
+One step = one pass of the whole path (block pooling, Stage 1 block filter, Stage 2 token
+refinement: Algorithm 1 of the paper) over one batch of synthetic queries whose inputs are already
+resident in HBM.  The default workload is the 64K-context prefill (B=128, m=64, k=2048, H=64,
+d=128, bf16): the shape the headline metric "indexer queries/s at 64K context" is quoted on.
+The flat DSA indexer (Eqs. 1-2) is timed at the same shape for the speedup ratio, the Stage 2
+kernel is timed alone for the roofline figure, and the CPU oracle is timed on a bounded sample of
+the same queries as a reported baseline.
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def algorithmic_pairs(wl):
+    """(Stage 1 block scores, Stage 2 token scores, flat token scores) the method must compute:
+    causal, selected, no padding (Eqs. 10-11 of the paper, counted exactly)."""
+    pos = wl.positions()
+    b_t = pos // wl.B
+    stage1 = int((b_t + 1).sum())
+    nblk = np.minimum(wl.m, b_t + 1)
+    stage2 = int(((nblk - 1) * wl.B + (pos % wl.B) + 1).sum())
+    flat = int((pos + 1).sum())
+    return stage1, stage2, flat
+
+
+def _iou(a, b):
+    """Eq. 12 of the paper on two index rows (-1 = padding): a host-side diagnostic."""
+    a, b = a[a >= 0], b[b >= 0]
+    u = np.union1d(a, b).size
+    return 1.0 if u == 0 else np.intersect1d(a, b).size / u
+
+
+def time_region(fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return e0.elapsed_time(e1) / steps, wall
+
+
+def cpu_baseline(wl, budget_s=20.0, seed=0):
+    """The oracle as it stands, on the host cores, on a bounded uniform sample of the queries."""
+    from oracle import hisa_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    except Exception:
+        cores = 1
+    rng = np.random.default_rng(seed)
+    pos = wl.positions()
+    args = dict(q=wl.q, q_dtype=wl.q_dtype, w=wl.w, q_seq=wl.q_seq, q_pos=pos, keys=wl.keys,
+                k_dtype=wl.k_dtype, k_scale=wl.k_scale, seq_len=wl.seq_len, B=wl.B, m=wl.m, k=wl.k,
+                pooled_dtype=wl.pooled_dtype)
+    t0 = time.perf_counter()
+    pooled = O.pool_blocks(wl.keys, wl.k_dtype, wl.k_scale, wl.seq_len, wl.B, wl.pooled_dtype)
+    t_pool = time.perf_counter() - t0
+    done, spent, n = 0, 0.0, 8
+    while spent < budget_s and done < wl.T:
+        qs = rng.choice(wl.T, size=min(n, wl.T), replace=False)
+        t0 = time.perf_counter()
+        O.hisa_indexer(**args, queries=qs, pooled=pooled)
+        spent += time.perf_counter() - t0
+        done += qs.size
+        n = min(n * 2, 256)
+    return {"value": done / spent, "unit": "queries/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{done} queries drawn uniformly from the {wl.T} of the workload, Stage 1 + Stage 2 in "
+                      f"float64 numpy ({spent:.1f} s); pooling all keys once took {t_pool:.2f} s extra"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="prefill64k_bf16")
+    ap.add_argument("--flat-steps", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-flat", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the indexer shards by query with no exchange; "
+              "see DESIGN.md); --gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2603_28458_amd import hisa
+    from paper_2603_28458_amd import workloads as W
+
+    hisa.lib()                                  # fail loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    wl = W.config(a.workload)
+    Q, K = hisa.to_device(wl)
+    pd = hisa.DTYPE_CODE[wl.pooled_dtype]
+    T, M = wl.T, wl.s_max // wl.B
+    dev = Q.q.device
+    decode = wl.q_seq is not None
+
+    pooled = torch.zeros((wl.n_seq, M, wl.d), dtype=torch.bfloat16 if pd == hisa.HISA_BF16 else torch.float32,
+                         device=dev)
+    block_idx = torch.empty((T, wl.m), dtype=torch.int32, device=dev)
+    topk_idx = torch.empty((T, wl.k), dtype=torch.int32, device=dev)
+    ws1 = torch.empty(max(1, hisa.hisa_workspace_bytes(hisa.OP_BLOCK_SCORE_TOPK, Q, K, wl.B, wl.m, wl.k)),
+                      dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(max(1, hisa.hisa_workspace_bytes(hisa.OP_TOKEN_REFINE_TOPK, Q, K, wl.B, wl.m, wl.k)),
+                      dtype=torch.uint8, device=dev)
+
+    def pool():
+        hisa.hisa_pool_blocks(K, wl.B, pooled=pooled, pooled_dtype=pd)
+
+    def stage1():
+        hisa.hisa_block_score_topk(Q, K, pooled, pd, wl.B, wl.m, block_idx=block_idx, ws=ws1)
+
+    def stage2():
+        hisa.hisa_token_refine_topk(Q, K, wl.B, wl.m, block_idx, wl.k, topk_idx=topk_idx, ws=ws2)
+
+    def step():
+        if not decode:          # decode: the pooled cache is precomputed (maintained with the KV cache)
+            pool()
+        stage1()
+        stage2()
+
+    pool()
+    ms_step, wall_step = time_region(step, a.steps, a.warmup)
+    ms_pool, _ = time_region(pool, a.steps, 1)
+    ms_s1, _ = time_region(stage1, a.steps, 1)
+    ms_s2, _ = time_region(stage2, a.steps, 1)     # Stage 2 alone: the dominant kernel
+
+    p1, p2, pf = algorithmic_pairs(wl)
+    flop_pair = 2.0 * wl.H * wl.d
+    fused = wl.q_dtype == "bf16" and T >= 256 and wl.m * wl.B <= 16384
+    if decode:
+        kb = {"bf16": 2, "fp8_e4m3": 1, "f32": 4}[wl.k_dtype] * wl.d + (4 if wl.k_dtype == "fp8_e4m3" else 0)
+        bytes_s2 = p2 * kb + T * (wl.H * wl.d * 2 + wl.H * 4 + wl.m * 4 + wl.k * 4) + 2 * p2 * 4
+        roof = {"bound": "hbm", "achieved": bytes_s2 / (ms_s2 * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "kernel": "hisa_token_refine_topk (k_score_ranges + k_select)", "traffic": None}
+    else:
+        roof = {"bound": "mfma", "achieved": p2 * flop_pair / (ms_s2 * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "kernel": "k_refine_fused" if fused else "k_score_ranges + k_select",
+                "traffic": None}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["ms_per_launch"] = ms_s2
+
+    out = {
+        "metric": "indexer queries/s at 64K context (HISA: pool + Stage 1 + Stage 2)" if "64k" in a.workload
+                  else f"indexer queries/s ({a.workload})",
+        "value": T / (ms_step * 1e-3), "unit": "queries/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.q_dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": a.workload, "T": T, "L": int(wl.seq_len.max()), "n_seq": wl.n_seq, "H": wl.H,
+                   "d": wl.d, "B": wl.B, "m": wl.m, "k": wl.k, "q_dtype": wl.q_dtype, "k_dtype": wl.k_dtype},
+        "stage_ms": {"pool": ms_pool, "stage1": ms_s1, "stage2": ms_s2, "wall_ms_per_step": wall_step},
+        "algorithmic": {"stage1_pairs": p1, "stage2_pairs": p2, "flat_pairs": pf, "flop_per_pair": flop_pair,
+                        "hisa_tflop": (p1 + p2) * flop_pair / 1e12, "flat_tflop": pf * flop_pair / 1e12},
+        "roofline": roof,
+    }
+
+    if not a.no_flat:
+        ws_f = torch.empty(hisa.hisa_workspace_bytes(hisa.OP_FLAT_TOPK, Q, K, 1, 0, wl.k), dtype=torch.uint8, device=dev)
+        flat_idx = torch.empty((T, wl.k), dtype=torch.int32, device=dev)
+
+        def flat():
+            hisa.dsa_flat_indexer_topk(Q, K, wl.k, topk_idx=flat_idx, ws=ws_f)
+
+        ms_flat, _ = time_region(flat, a.flat_steps, 1)
+        out["flat"] = {"ms": ms_flat, "queries_per_s": T / (ms_flat * 1e-3),
+                       "tflops": pf * flop_pair / (ms_flat * 1e-3) / 1e12,
+                       "frac_of_mfma_peak": pf * flop_pair / (ms_flat * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+        out["speedup_vs_flat"] = ms_flat / ms_step
+        a_idx, b_idx = topk_idx.cpu().numpy(), flat_idx.cpu().numpy()
+        rng = np.random.default_rng(0)
+        out["iou_hisa_vs_flat_sampled"] = float(np.mean([_iou(a_idx[t], b_idx[t])
+                                                         for t in rng.choice(T, size=min(T, 512), replace=False)]))
+        del ws_f
+
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -17,6 +17,7 @@ torch's CPU conversion routines) is part of producing the inputs, not of the ind
 """
 from __future__ import annotations
 
+import os
 from dataclasses import dataclass, field
 from typing import Optional
 
@@ -27,13 +28,36 @@ F32, BF16, FP8 = "f32", "bf16", "fp8_e4m3"
 BASE_SEED = 20260328
 
 
+_N_STREAMS = 16   # fixed, so the drawn values do not depend on the machine's core count
+
+
+def _normal(ss: np.random.SeedSequence, shape) -> np.ndarray:
+    """N(0,1) float32 array of `shape`, drawn as _N_STREAMS independent child streams over equal
+    slices of the first axis (filled in parallel: numpy releases the GIL while drawing)."""
+    from concurrent.futures import ThreadPoolExecutor
+    out = np.empty(shape, dtype=np.float32)
+    n = shape[0]
+    bounds = [(i * n) // _N_STREAMS for i in range(_N_STREAMS + 1)]
+    kids = ss.spawn(_N_STREAMS)
+
+    def fill(i):
+        lo, hi = bounds[i], bounds[i + 1]
+        if hi > lo:
+            np.random.default_rng(kids[i]).standard_normal(out=out[lo:hi], dtype=np.float32)
+
+    with ThreadPoolExecutor(max_workers=min(_N_STREAMS, os.cpu_count() or 1)) as ex:
+        list(ex.map(fill, range(_N_STREAMS)))
+    return out
+
+
 def _to_bf16_bits(x: np.ndarray) -> np.ndarray:
     t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16)
     return t.view(torch.int16).numpy().view(np.uint16)
 
 
 def _bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
-    return (b.astype(np.uint32) << 16).view(np.float32)
+    t = torch.from_numpy(np.ascontiguousarray(b).view(np.int16)).view(torch.bfloat16)
+    return t.to(torch.float32).numpy()
 
 
 def _to_fp8(x: np.ndarray):
@@ -110,7 +134,8 @@ def make_workload(name: str, *, n_seq: int = 1, seq_len, T: int, H: int, d: int,
     mode = "decode" : n_seq sequences, one query each at its sequence's last position (T == n_seq).
     seq_len: int, or a sequence of n_seq ints.
     """
-    rng = np.random.default_rng(seed)
+    ss_q, ss_k, ss_misc = np.random.SeedSequence(seed).spawn(3)
+    rng = np.random.default_rng(ss_misc)
     seq_len = np.atleast_1d(np.asarray(seq_len, dtype=np.int64))
     if seq_len.size == 1 and n_seq > 1:
         seq_len = np.repeat(seq_len, n_seq)
@@ -122,9 +147,7 @@ def make_workload(name: str, *, n_seq: int = 1, seq_len, T: int, H: int, d: int,
         pooled_dtype = F32 if k_dtype == F32 else BF16
 
     # queries and gates first (needles point at them)
-    qf = rng.standard_normal((T, H, d), dtype=np.float32)
-    q_bits = _cast(qf, q_dtype)
-    qf = _as_f32(q_bits, q_dtype)
+    q_bits = _cast(_normal(ss_q, (T, H, d)), q_dtype)
     w = rng.random((T, H), dtype=np.float32)
 
     if mode == "prefill":
@@ -162,16 +185,18 @@ def make_workload(name: str, *, n_seq: int = 1, seq_len, T: int, H: int, d: int,
         j_star = int(rng.integers(0, H))
         needles.append((n, p, t_star, j_star))
 
+    ss_seq = ss_k.spawn(n_seq)
     for n in range(n_seq):
         Ln = int(seq_len[n])
         nb = -(-Ln // B)
-        cent = rng.standard_normal((nb, d), dtype=np.float32)
-        kf = rng.standard_normal((Ln, d), dtype=np.float32)
+        ss_c, ss_t = ss_seq[n].spawn(2)
+        cent = _normal(ss_c, (nb, d))
+        kf = _normal(ss_t, (Ln, d))
         kf *= np.float32(0.5)
         kf += np.repeat(cent, B, axis=0)[:Ln]
         for (nn, p, t_star, j_star) in needles:
             if nn == n:
-                v = qf[t_star, j_star]
+                v = _as_f32(q_bits[t_star, j_star], q_dtype)
                 kf[p] = np.float32(3.0 * np.sqrt(1.25 * d)) * v / np.linalg.norm(v)
         if k_dtype == FP8:
             codes, sc = _to_fp8(kf)

@@ -44,7 +44,7 @@ def sample_queries(wl, n, seed=0):
     return np.array(sorted(pick), dtype=np.int64)
 
 
-def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False):
+def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, flat_queries=None):
     """Runs the four entry points on `wl` and checks them on `queries` (all if None).
     Returns a dict of statistics (max relative score error, number of threshold swaps)."""
     rtol = rtol_for(wl)
@@ -132,9 +132,10 @@ def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False):
         fl_idx, fl_sc = hisa.dsa_flat_indexer_topk(Q, K, wl.k, want_topk_scores=True)
         torch.cuda.synchronize()
         fi, fs = _np(fl_idx), _np(fl_sc)
-        o_fi, o_fs, rows = O.dsa_flat_indexer_topk(**oracle_args(wl), k=wl.k, queries=qs, return_scores=True)
+        fq = qs if flat_queries is None else np.asarray(flat_queries)
+        o_fi, o_fs, rows = O.dsa_flat_indexer_topk(**oracle_args(wl), k=wl.k, queries=fq, return_scores=True)
         swaps = 0
-        for i, t in enumerate(qs):
+        for i, t in enumerate(fq):
             ids = np.arange(rows[i].size)
             swaps += check_set(fi[t], o_fi[i], ids, rows[i], rtol, f"flat set of query {t}")
             nv = int((fi[t] >= 0).sum())

@@ -1,0 +1,40 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times: the library
+runs on ALL queries of each configuration and the oracle checks a stratified sample of them
+(uniform positions, the regime boundaries of Section 4.1, block edges, needle targets), since the
+flat oracle over every query of a 64K context would take hours."""
+import numpy as np
+import pytest
+
+from paper_2603_28458_amd import workloads as W
+from tests.parity import run_and_check, sample_queries
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(name, n_hisa, n_flat):
+    wl = W.config(name)
+    qs = sample_queries(wl, n_hisa, seed=1)
+    fq = qs if n_flat is None else sample_queries(wl, n_flat, seed=2)[:: max(1, len(qs) // max(1, n_flat))][:n_flat]
+    print(f"\n[parity-full] {name}: T={wl.T} L={int(wl.seq_len.max())} n_seq={wl.n_seq} B={wl.B} m={wl.m} k={wl.k} "
+          f"k_dtype={wl.k_dtype}; oracle on {len(qs)} queries (flat on {len(fq)})", flush=True)
+    return run_and_check(wl, queries=qs, flat_queries=fq, verbose=True)
+
+
+def test_config2_prefill_16k_bf16():
+    _run("prefill16k_bf16", 96, None)
+
+
+def test_config3_prefill_64k_bf16():
+    _run("prefill64k_bf16", 64, 24)
+
+
+def test_config3_prefill_64k_fp8():
+    _run("prefill64k_fp8", 64, 24)
+
+
+def test_config4_decode_32x128k():
+    _run("decode32x128k_bf16", 32, None)
+
+
+def test_config5_chunk_16k_against_1m_fp8():
+    _run("chunk16k_1m_fp8", 48, 6)
