@@ -75,6 +75,28 @@ __device__ __forceinline__ void load_qfrag(QFrag<HG>& f, const uint16_t* __restr
   }
 }
 
+// Makes every load behind the fragment complete HERE.  Without it the first use sits inside the
+// tile loop, and the in-order load counter then also waits there, every iteration, for the key
+// rows that were just prefetched.
+template <int HG>
+__device__ __forceinline__ void qfrag_ready(QFrag<HG>& f) {
+#pragma unroll
+  for (int g = 0; g < HG; ++g) {
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) asm volatile("" : "+v"(f.a[g][kk]));
+#pragma unroll
+    for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(f.w[g][i]));
+  }
+}
+
+// max(x, 0) in one instruction (the float max costs a second one that quiets NaNs first).
+__device__ __forceinline__ float relu(float x) {
+  // as signed integers, every negative float (and -0) is below 0 and every positive float keeps
+  // its bits: one integer max, with no NaN-quieting instruction in front of it
+  const int b = __builtin_bit_cast(int, x);
+  return __builtin_bit_cast(float, b > 0 ? b : 0);
+}
+
 // Score of the 32 keys of a staged tile against every head of the query:
 // sum_j w_j * max(0, q_j . k).  Every lane returns the score of key (lane % 32).
 template <int HG>
@@ -90,20 +112,27 @@ __device__ __forceinline__ float score_tile(const QFrag<HG>& f, const uint4* til
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) {
     const int c = 2 * kk + half;
+#ifdef HISA_EXP_NO_LDSREAD
+    const bf16x8 kv = f.a[0][kk ^ 1];
+#else
     const bf16x8 kv = as_bf16x8(tile[r * 16 + (c ^ (r & 15))]);
+#endif
 #pragma unroll
     for (int g = 0; g < HG; ++g)
       acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[g][kk], kv, acc[g], 0, 0, 0);
   }
   float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#ifdef HISA_EXP_NO_EPILOGUE
+  return acc[0][0] + acc[HG - 1][5];
+#endif
 #pragma unroll
   for (int g = 0; g < HG; ++g) {
 #pragma unroll
     for (int i = 0; i < 16; i += 4) {
-      s0 = __builtin_fmaf(__builtin_fmaxf(acc[g][i + 0], 0.f), f.w[g][i + 0], s0);
-      s1 = __builtin_fmaf(__builtin_fmaxf(acc[g][i + 1], 0.f), f.w[g][i + 1], s1);
-      s2 = __builtin_fmaf(__builtin_fmaxf(acc[g][i + 2], 0.f), f.w[g][i + 2], s2);
-      s3 = __builtin_fmaf(__builtin_fmaxf(acc[g][i + 3], 0.f), f.w[g][i + 3], s3);
+      s0 = __builtin_fmaf(relu(acc[g][i + 0]), f.w[g][i + 0], s0);
+      s1 = __builtin_fmaf(relu(acc[g][i + 1]), f.w[g][i + 1], s1);
+      s2 = __builtin_fmaf(relu(acc[g][i + 2]), f.w[g][i + 2], s2);
+      s3 = __builtin_fmaf(relu(acc[g][i + 3]), f.w[g][i + 3], s3);
     }
   }
   float s = (s0 + s1) + (s2 + s3);
@@ -150,6 +179,44 @@ __device__ __forceinline__ u32x32 tile_fetch_bf16(const uint16_t* __restrict__ b
   return v;
 }
 
+// The same fetch for a tile that lies wholly inside the key array: a wave-uniform tile base plus
+// eight per-lane byte offsets that do not depend on the tile (computed once per kernel).
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ u32x8 tile_lane_offsets_bf16() {
+  const int lane = lane_id();
+  u32x8 o;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int r = 4 * i + (lane >> 4), c = lane & 15;
+    o[i] = (uint32_t)(r * 256 + ((c ^ (r & 15)) << 4));
+  }
+  return o;
+}
+
+// Key rows are read through a raw buffer descriptor: base = the sequence's first key, a
+// wave-uniform byte offset picks the tile, the per-lane offsets stay in registers for the whole
+// kernel, and reads past the end of the sequence's key array return zeros instead of faulting.
+typedef uint32_t u32x4v __attribute__((__vector_size__(16)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t key_buffer(const void* base, long bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ u32x32 tile_fetch_bf16(__amdgpu_buffer_rsrc_t rsrc, int tile_byte_off,
+                                                  const u32x8& o) {
+  u32x32 v;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const u32x4v x = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)o[i], tile_byte_off, 0);
+    v[4 * i + 0] = x[0];
+    v[4 * i + 1] = x[1];
+    v[4 * i + 2] = x[2];
+    v[4 * i + 3] = x[3];
+  }
+  return v;
+}
+
 __device__ __forceinline__ void tile_store_bf16(uint4* tile, const u32x32& v) {
   const int lane = lane_id();
 #pragma unroll
@@ -179,6 +246,21 @@ __device__ __forceinline__ u32x16 tile_fetch_fp8(const uint8_t* __restrict__ bas
     long gr = row0 + r;
     gr = gr < n_rows ? gr : n_rows - 1;
     put4(v, i, *reinterpret_cast<const uint4*>(base + gr * kD + (c8 << 4)));
+  }
+  return v;
+}
+
+// Whole-tile fetch of fp8 keys: the 4 KB of a tile are contiguous and taken in lane order.
+__device__ __forceinline__ u32x16 tile_fetch_fp8(__amdgpu_buffer_rsrc_t rsrc, int tile_byte_off) {
+  const int o = lane_id() << 4;
+  u32x16 v;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const u32x4v x = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o + i * 1024, tile_byte_off, 0);
+    v[4 * i + 0] = x[0];
+    v[4 * i + 1] = x[1];
+    v[4 * i + 2] = x[2];
+    v[4 * i + 3] = x[3];
   }
   return v;
 }

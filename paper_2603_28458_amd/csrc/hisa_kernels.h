@@ -189,6 +189,16 @@ __device__ __forceinline__ void tile_fetch(TileRegs<KDT>& r, const void* base, l
     r.v = tile_fetch_fp8((const uint8_t*)base, row0, n_rows);
 }
 
+// Fetch through the sequence's buffer descriptor (tile_byte_off is wave-uniform).
+template <int KDT>
+__device__ __forceinline__ void tile_fetch_buf(TileRegs<KDT>& r, __amdgpu_buffer_rsrc_t rsrc,
+                                               int tile_byte_off, const u32x8& lane_offs) {
+  if constexpr (KDT == DT_BF16)
+    r.v = tile_fetch_bf16(rsrc, tile_byte_off, lane_offs);
+  else
+    r.v = tile_fetch_fp8(rsrc, tile_byte_off);
+}
+
 template <int KDT>
 __device__ __forceinline__ void tile_store(uint4* tile, const TileRegs<KDT>& r) {
   if constexpr (KDT == DT_BF16)
@@ -243,6 +253,7 @@ __global__ __launch_bounds__(256) void k_score_ranges(ScoreArgs a) {
   QFrag<HG> f;
   load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
 
+  qfrag_ready<HG>(f);
   TileRegs<KDT> regs;
   for (int i = 0; i < a.tiles_per_wave; ++i) {
     const int v = v0 + wave + 4 * i;
@@ -330,6 +341,7 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
     fetch(0);
     store(0);
   }
+  qfrag_ready<HG>(f);
   __syncthreads();
   int cur = 0;
   for (int it = 0; it < n_iter; ++it) {
@@ -431,8 +443,10 @@ __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int
   const int n_slots = a.m * a.B;
   SelectSmem<256, E>& sm =
       *reinterpret_cast<SelectSmem<256, E>*>(smem + 4 * kTileChunks * 16 + (size_t)n_slots * 4);
+  int32_t* blk_ids = reinterpret_cast<int32_t*>(smem + 4 * kTileChunks * 16 + (size_t)n_slots * 4 +
+                                                sizeof(SelectSmem<256, E>));
   const int t = a.t_begin + (gridDim.x - 1 - blockIdx.x);
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   int seq;
   const int pos = query_pos(a, t, seq);
   const int n_vis = pos + 1;
@@ -444,22 +458,54 @@ __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int
   QFrag<HG> f;
   load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
 
+  // kept block ids of this query: tile v = sub-tile v % tpb of slot v / tpb
+  for (int i = threadIdx.x; i < a.m; i += 256) blk_ids[i] = a.block_idx[(long)t * a.m + i];
+  __syncthreads();
+  qfrag_ready<HG>(f);
+  const int tpb = a.B >> 5;
+  const int n_blocks = (int)(a.rows_per_seq / a.B);
+  // first key row of tile v, or -1 if its slot is empty / out of range / not visible (wave-uniform)
+  auto row_of = [&](int v) -> int {
+    const int slot = v / tpb;
+    const int blk = __builtin_amdgcn_readfirstlane(blk_ids[slot]);
+    const int row0 = blk * a.B + (v - slot * tpb) * 32;
+    return (blk < 0 || blk >= n_blocks || row0 >= n_vis) ? -1 : row0;
+  };
+  const int row_bytes = kD * rb;
+  const u32x8 lane_offs = tile_lane_offsets_bf16();
+  const __amdgpu_buffer_rsrc_t krsrc = key_buffer(kbase, a.rows_per_seq * row_bytes);
+
+  // Each wave walks its tiles with the next tile's key rows already in flight (registers) while
+  // the current one is multiplied: global latency hides behind the MFMAs.
   uint4* my = stage + wave * kTileChunks;
   TileRegs<KDT> regs;
+  int row_next = wave < n_tiles ? row_of(wave) : -1;
+  if (row_next >= 0) tile_fetch_buf<KDT>(regs, krsrc, row_next * row_bytes, lane_offs);
+#ifdef HISA_EXP_SKIP_SCORE
+  for (int v = n_tiles + wave; v < n_tiles; v += 4) {
+#else
   for (int v = wave; v < n_tiles; v += 4) {
-    const TileLoc L = tile_loc(a, t, v, true);
+#endif
+    const int row0 = row_next;
     float s = neg_inf();
-    if (L.row0 >= 0 && L.row0 < n_vis) {
-      tile_fetch<KDT>(regs, kbase, L.row0, a.rows_per_seq);
+    if (row0 >= 0) {
       wave_lds_sync();
+#ifndef HISA_EXP_NO_STORE
       tile_store<KDT>(my, regs);
+#endif
+    }
+    row_next = (v + 4 < n_tiles) ? row_of(v + 4) : -1;
+#ifndef HISA_EXP_NO_FETCH
+    if (row_next >= 0) tile_fetch_buf<KDT>(regs, krsrc, row_next * row_bytes, lane_offs);
+#endif
+    if (row0 >= 0) {
       wave_lds_sync();
       s = score_tile<HG>(f, my);
-      const long row = L.row0 + (lane & 31);
-      if (KDT == DT_FP8) s *= sbase[row < a.rows_per_seq ? row : a.rows_per_seq - 1];
+      const int row = row0 + (lane & 31);
+      if (KDT == DT_FP8) s *= sbase[row];
       if (row >= n_vis) s = neg_inf();
     }
-    if (lane < 32) sc[L.out0 + lane] = s;
+    if (lane < 32) sc[v * 32 + lane] = s;
   }
   __syncthreads();
 
@@ -468,9 +514,13 @@ __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int
   auto load = [&](int i) -> uint32_t { return ordered_key(sc[i]); };
   auto emit = [&](int p, int i, uint32_t key) {
     const int slot = i / a.B;
-    oi[p] = a.block_idx[(long)t * a.m + slot] * a.B + (i - slot * a.B);
+    oi[p] = blk_ids[slot] * a.B + (i - slot * a.B);
     if (os) os[p] = key_to_score(key);
   };
+#ifdef HISA_EXP_SKIP_SELECT
+  if (threadIdx.x < 32) oi[threadIdx.x] = (int)sc[threadIdx.x * 7];
+  return;
+#endif
   const int n_out = select_topk<256, E>(sm, n_slots, k, load, emit);
   for (int p = n_out + threadIdx.x; p < k; p += 256) {
     oi[p] = -1;
