@@ -63,6 +63,19 @@ def time_region(fn, steps, warmup):
     return e0.elapsed_time(e1) / steps, wall
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary
+    (profiles/hbm_traffic_<workload>.txt: FETCH_SIZE and WRITE_SIZE scaled by a copy of known size);
+    None if that workload has not been profiled."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch="):
+            return float(line.split("=", 1)[1])
+    return None
+
+
 def cpu_baseline(wl, budget_s=20.0, seed=0):
     """The oracle as it stands, on the host cores, on a bounded uniform sample of the queries."""
     from oracle import hisa_oracle as O
@@ -101,6 +114,9 @@ def main():
     ap.add_argument("--flat-steps", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-flat", action="store_true")
+    ap.add_argument("--profile-mode", action="store_true",
+                    help="for rocprofv3: run the step a few times plus a 256 MiB device copy (counter "
+                         "calibration), print nothing else and exit")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the indexer shards by query with no exchange; "
@@ -145,6 +161,17 @@ def main():
         stage2()
 
     pool()
+    if a.profile_mode:
+        for _ in range(max(1, a.steps)):
+            step()
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)     # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"profile_mode": True, "workload": a.workload, "steps": a.steps,
+                          "calibration_copy_bytes": src.numel() * 4}))
+        return
     ms_step, wall_step = time_region(step, a.steps, a.warmup)
     ms_pool, _ = time_region(pool, a.steps, 1)
     ms_s1, _ = time_region(stage1, a.steps, 1)
@@ -164,6 +191,7 @@ def main():
                 "traffic": None}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["ms_per_launch"] = ms_s2
+    roof["traffic"] = measured_traffic(a.workload)
 
     out = {
         "metric": "indexer queries/s at 64K context (HISA: pool + Stage 1 + Stage 2)" if "64k" in a.workload

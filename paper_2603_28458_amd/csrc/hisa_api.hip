@@ -155,8 +155,9 @@ SelectArgs select_base(const hisa_queries* q, const hisa_keys* k) {
 template <int HG, int KDT, int E>
 int launch_fused_hg(const ScoreArgs& a, int k, int32_t* topk_idx, float* topk_scores,
                     hipStream_t st) {
-  const size_t sh = 4 * kTileChunks * 16 + (size_t)a.m * a.B * 4 + sizeof(SelectSmem<256, E>) +
-                    (size_t)a.m * 4;
+  const size_t sh = (size_t)4 * kNBuf * kTileChunks * 16 + (size_t)a.m * a.B * 4 +
+                    sizeof(SelectSmem<256, E>) +
+                    (size_t)a.m * 4 + 16;
   auto kern = k_refine_fused<HG, KDT, E>;
   // more than 64 KB of LDS per workgroup has to be asked for explicitly
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),

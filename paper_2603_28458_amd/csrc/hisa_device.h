@@ -112,19 +112,12 @@ __device__ __forceinline__ float score_tile(const QFrag<HG>& f, const uint4* til
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) {
     const int c = 2 * kk + half;
-#ifdef HISA_EXP_NO_LDSREAD
-    const bf16x8 kv = f.a[0][kk ^ 1];
-#else
     const bf16x8 kv = as_bf16x8(tile[r * 16 + (c ^ (r & 15))]);
-#endif
 #pragma unroll
     for (int g = 0; g < HG; ++g)
       acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[g][kk], kv, acc[g], 0, 0, 0);
   }
   float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-#ifdef HISA_EXP_NO_EPILOGUE
-  return acc[0][0] + acc[HG - 1][5];
-#endif
 #pragma unroll
   for (int g = 0; g < HG; ++g) {
 #pragma unroll
@@ -140,6 +133,116 @@ __device__ __forceinline__ float score_tile(const QFrag<HG>& f, const uint4* til
   return s;
 }
 
+// The same contraction and epilogue as two separate steps, so that a kernel can overlap the
+// epilogue of one tile with the MFMAs of the next (software pipelining inside one wave).
+template <int HG>
+using accvec = float __attribute__((ext_vector_type(16 * HG)));
+typedef uint32_t u32x32 __attribute__((ext_vector_type(32)));
+
+// B operands of one staged tile: 8 chunks per lane, chunk kk = contraction step kk.
+__device__ __forceinline__ u32x32 lds_read_tile(const uint4* tile) {
+  const int lane = lane_id();
+  const int half = lane >> 5;
+  const int r = lane & 31;
+  u32x32 kv;
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    const uint4 x = tile[r * 16 + ((2 * kk + half) ^ (r & 15))];
+    kv[4 * kk + 0] = x.x;
+    kv[4 * kk + 1] = x.y;
+    kv[4 * kk + 2] = x.z;
+    kv[4 * kk + 3] = x.w;
+  }
+  return kv;
+}
+
+// The same reads issued as raw instructions, for a ring of several tiles per wave: for a plain LDS load the compiler first waits for
+// EVERY pending global->LDS transfer of the wave, which would undo the look-ahead of the tile
+// ring.  The caller waits for the tile's DMA before calling; the data is complete on return.
+typedef uint32_t u32x4e __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ u32x32 lds_read_tile_raw(uint32_t tile_addr) {
+  const int lane = lane_id();
+  const int half = lane >> 5;
+  const int r = lane & 31;
+  u32x32 kv;
+  uint32_t ad[8];
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk)
+    ad[kk] = tile_addr + (uint32_t)((r * 16 + ((2 * kk + half) ^ (r & 15))) << 4);
+  u32x4e x0, x1, x2, x3, x4, x5, x6, x7;
+  // the reads and the wait for their data are one unit, so nothing that uses the data can be
+  // scheduled in front of the wait
+  asm volatile(
+      "ds_read_b128 %0, %8\n\t"
+      "ds_read_b128 %1, %9\n\t"
+      "ds_read_b128 %2, %10\n\t"
+      "ds_read_b128 %3, %11\n\t"
+      "ds_read_b128 %4, %12\n\t"
+      "ds_read_b128 %5, %13\n\t"
+      "ds_read_b128 %6, %14\n\t"
+      "ds_read_b128 %7, %15\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(x0), "=&v"(x1), "=&v"(x2), "=&v"(x3), "=&v"(x4), "=&v"(x5), "=&v"(x6), "=&v"(x7)
+      : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3]), "v"(ad[4]), "v"(ad[5]), "v"(ad[6]), "v"(ad[7])
+      : "memory");
+  const u32x4e xs[8] = {x0, x1, x2, x3, x4, x5, x6, x7};
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    kv[4 * kk + 0] = xs[kk][0];
+    kv[4 * kk + 1] = xs[kk][1];
+    kv[4 * kk + 2] = xs[kk][2];
+    kv[4 * kk + 3] = xs[kk][3];
+  }
+  return kv;
+}
+
+template <int HG>
+__device__ __forceinline__ accvec<HG> mfma_tile(const QFrag<HG>& f, const u32x32& kv) {
+  f32x16 acc[HG];
+#pragma unroll
+  for (int g = 0; g < HG; ++g)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[g][i] = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    const bf16x8 b =
+        as_bf16x8(make_uint4(kv[4 * kk + 0], kv[4 * kk + 1], kv[4 * kk + 2], kv[4 * kk + 3]));
+#pragma unroll
+    for (int g = 0; g < HG; ++g)
+      acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[g][kk], b, acc[g], 0, 0, 0);
+  }
+  accvec<HG> out;
+#pragma unroll
+  for (int g = 0; g < HG; ++g)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) out[g * 16 + i] = acc[g][i];
+  return out;
+}
+
+// Sum of both 32-lane halves in every lane (one swap of the halves, one add).
+__device__ __forceinline__ float add_halves(float s) {
+  const uint32_t b = __float_as_uint(s);
+  const auto sw = __builtin_amdgcn_permlane32_swap(b, b, false, false);
+  return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+}
+
+template <int HG>
+__device__ __forceinline__ float tile_epilogue(const QFrag<HG>& f, const accvec<HG>& acc) {
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+  for (int g = 0; g < HG; ++g) {
+#pragma unroll
+    for (int i = 0; i < 16; i += 4) {
+      s0 = __builtin_fmaf(relu(acc[g * 16 + i + 0]), f.w[g][i + 0], s0);
+      s1 = __builtin_fmaf(relu(acc[g * 16 + i + 1]), f.w[g][i + 1], s1);
+      s2 = __builtin_fmaf(relu(acc[g * 16 + i + 2]), f.w[g][i + 2], s2);
+      s3 = __builtin_fmaf(relu(acc[g * 16 + i + 3]), f.w[g][i + 3], s3);
+    }
+  }
+  return add_halves((s0 + s1) + (s2 + s3));
+}
+
 // ------------------------------------------------------------------------------------------
 // Tile staging.  Chunk (row r, 16-byte column c) of a tile lives at LDS chunk r*16 + (c ^ (r&15)).
 // A staging step moves chunk position p = i*64 + lane, so consecutive lanes write consecutive
@@ -147,7 +250,6 @@ __device__ __forceinline__ float score_tile(const QFrag<HG>& f, const uint4* til
 
 // The chunks a lane holds between fetch and store are kept in ONE vector value (not an array):
 // arrays that live across a barrier end up in scratch memory.
-typedef uint32_t u32x32 __attribute__((ext_vector_type(32)));
 typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
 
 template <class V>
@@ -249,6 +351,26 @@ __device__ __forceinline__ u32x16 tile_fetch_fp8(const uint8_t* __restrict__ bas
   }
   return v;
 }
+
+// The same tile moved global -> LDS directly (no registers): lane l of step i deposits its 16
+// bytes at LDS byte address lds_addr + (i*64 + l)*16, which is the staged layout above.
+typedef __attribute__((address_space(3))) void lds_void;
+
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+  return (uint32_t)reinterpret_cast<uintptr_t>(p);   // low 32 bits of a generic LDS pointer
+}
+
+__device__ __forceinline__ void tile_dma_bf16(__amdgpu_buffer_rsrc_t rsrc, uint32_t lds_addr,
+                                              int tile_byte_off, const u32x8& o) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(uintptr_t)(lds_addr + i * 1024), 16,
+                                         (int)o[i], tile_byte_off, 0, 0);
+}
+
+// Wait until every outstanding global load (vmcnt) / LDS access (lgkmcnt) of this wave is done.
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0f70); }
+__device__ __forceinline__ void wait_lds() { __builtin_amdgcn_s_waitcnt(0xc07f); }
 
 // Whole-tile fetch of fp8 keys: the 4 KB of a tile are contiguous and taken in lane order.
 __device__ __forceinline__ u32x16 tile_fetch_fp8(__amdgpu_buffer_rsrc_t rsrc, int tile_byte_off) {

@@ -6,7 +6,13 @@
 
 #include "hisa_device.h"
 
+#ifndef HISA_NBUF
+#define HISA_NBUF 1
+#endif
+
 namespace hisa {
+
+constexpr int kNBuf = HISA_NBUF;   // LDS tiles per wave in the fused Stage 2 kernel (DMA look-ahead)
 
 enum : int { DT_F32 = 0, DT_BF16 = 1, DT_FP8 = 2 };
 
@@ -439,18 +445,19 @@ __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int
                                                          float* topk_scores) {
   extern __shared__ __align__(16) unsigned char smem[];
   uint4* stage = reinterpret_cast<uint4*>(smem);                       // 4 x 8 KB
-  float* sc = reinterpret_cast<float*>(smem + 4 * kTileChunks * 16);   // m*B scores
+  constexpr size_t kStageBytes = (size_t)4 * kNBuf * kTileChunks * 16;
+  float* sc = reinterpret_cast<float*>(smem + kStageBytes);   // m*B scores
   const int n_slots = a.m * a.B;
   SelectSmem<256, E>& sm =
-      *reinterpret_cast<SelectSmem<256, E>*>(smem + 4 * kTileChunks * 16 + (size_t)n_slots * 4);
-  int32_t* blk_ids = reinterpret_cast<int32_t*>(smem + 4 * kTileChunks * 16 + (size_t)n_slots * 4 +
+      *reinterpret_cast<SelectSmem<256, E>*>(smem + kStageBytes + (size_t)n_slots * 4);
+  int32_t* blk_ids = reinterpret_cast<int32_t*>(smem + kStageBytes + (size_t)n_slots * 4 +
                                                 sizeof(SelectSmem<256, E>));
+  int32_t* n_used_p = blk_ids + a.m;
   const int t = a.t_begin + (gridDim.x - 1 - blockIdx.x);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   int seq;
   const int pos = query_pos(a, t, seq);
   const int n_vis = pos + 1;
-  const int n_tiles = n_slots >> 5;
   const int rb = KDT == DT_BF16 ? 2 : 1;
   const char* kbase = (const char*)a.keys + (long)seq * a.rows_per_seq * kD * rb;
   const float* sbase = a.k_scale ? a.k_scale + (long)seq * a.rows_per_seq : nullptr;
@@ -458,56 +465,122 @@ __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int
   QFrag<HG> f;
   load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
 
-  // kept block ids of this query: tile v = sub-tile v % tpb of slot v / tpb
-  for (int i = threadIdx.x; i < a.m; i += 256) blk_ids[i] = a.block_idx[(long)t * a.m + i];
-  __syncthreads();
-  qfrag_ready<HG>(f);
+  // kept block ids of this query; tile v = sub-tile v % tpb of slot v / tpb.  Only the slots up to
+  // the last kept block are walked (a short prefix keeps few blocks).
   const int tpb = a.B >> 5;
   const int n_blocks = (int)(a.rows_per_seq / a.B);
+  if (threadIdx.x == 0) *n_used_p = 0;
+  __syncthreads();
+  for (int i = threadIdx.x; i < a.m; i += 256) {
+    const int blk = a.block_idx[(long)t * a.m + i];
+    blk_ids[i] = blk;
+    if (blk >= 0 && blk < n_blocks) atomicMax(n_used_p, i + 1);
+  }
+  __syncthreads();
+  const int n_active = __builtin_amdgcn_readfirstlane(*n_used_p) * tpb;
+  qfrag_ready<HG>(f);
   // first key row of tile v, or -1 if its slot is empty / out of range / not visible (wave-uniform)
   auto row_of = [&](int v) -> int {
     const int slot = v / tpb;
-    const int blk = __builtin_amdgcn_readfirstlane(blk_ids[slot]);
+    const int blk = blk_ids[slot];
     const int row0 = blk * a.B + (v - slot * tpb) * 32;
     return (blk < 0 || blk >= n_blocks || row0 >= n_vis) ? -1 : row0;
   };
   const int row_bytes = kD * rb;
   const u32x8 lane_offs = tile_lane_offsets_bf16();
   const __amdgpu_buffer_rsrc_t krsrc = key_buffer(kbase, a.rows_per_seq * row_bytes);
+  uint4* my = stage + wave * kNBuf * kTileChunks;
+  const int nj = n_active > wave ? (n_active - wave + 3) >> 2 : 0;   // tiles of this wave
 
-  // Each wave walks its tiles with the next tile's key rows already in flight (registers) while
-  // the current one is multiplied: global latency hides behind the MFMAs.
-  uint4* my = stage + wave * kTileChunks;
-  TileRegs<KDT> regs;
-  int row_next = wave < n_tiles ? row_of(wave) : -1;
-  if (row_next >= 0) tile_fetch_buf<KDT>(regs, krsrc, row_next * row_bytes, lane_offs);
-#ifdef HISA_EXP_SKIP_SCORE
-  for (int v = n_tiles + wave; v < n_tiles; v += 4) {
-#else
-  for (int v = wave; v < n_tiles; v += 4) {
-#endif
-    const int row0 = row_next;
-    float s = neg_inf();
-    if (row0 >= 0) {
-      wave_lds_sync();
-#ifndef HISA_EXP_NO_STORE
-      tile_store<KDT>(my, regs);
-#endif
+  if constexpr (KDT == DT_BF16) {
+    // Software pipeline inside the wave: while the MFMAs of tile j+1 run, the ReLU / gate /
+    // head-sum epilogue of tile j executes on the vector ALU and the key rows of tile j+2 travel
+    // global -> LDS.  One 8 KB LDS tile per wave suffices: its rows are copied into registers
+    // (B operands) before the next DMA is issued.  The loop is unrolled by two so that the two
+    // accumulator sets swap roles without being copied.
+    const uint32_t my_addr = lds_address(my);
+    // first key row of this wave's j-th tile: lane j (of two registers) holds it
+    const int rows_lo = row_of(wave + 4 * (lane < nj ? lane : 0));
+    const int rows_hi = (nj > 64) ? row_of(wave + 4 * (lane + 64 < nj ? lane + 64 : 0)) : -1;
+    auto row_at = [&](int j) -> int {
+      return j < 64 ? __builtin_amdgcn_readlane(rows_lo, j) : __builtin_amdgcn_readlane(rows_hi, j - 64);
+    };
+    // tile j lives in (and is DMA'd into) LDS buffer j % kNBuf of this wave
+    auto dma = [&](int j, int buf) {
+      const int r = row_at(j);
+      tile_dma_bf16(krsrc, my_addr + buf * (kTileChunks * 16), (r < 0 ? 0 : r) * row_bytes, lane_offs);
+    };
+    auto finish = [&](int j, float s) {
+      const int r = row_at(j);
+      const int row = (r < 0 ? 0 : r) + (lane & 31);
+      if (row >= (r < 0 ? 0 : n_vis)) s = neg_inf();
+      if (lane < 32) sc[(wave + 4 * j) * 32 + lane] = s;
+    };
+    // the DMA of tile j is complete once at most 8 * (tiles issued after it) loads are pending
+    auto wait_tile = [&](int j) {
+      const int later = (nj - 1 - j) < (kNBuf - 1) ? (nj - 1 - j) : (kNBuf - 1);
+      if (later >= 2) __builtin_amdgcn_s_waitcnt(0x4f70);        // vmcnt(16)
+      else if (later == 1) __builtin_amdgcn_s_waitcnt(0x0f78);   // vmcnt(8)
+      else wait_vmem();
+    };
+    int buf = 0;   // buffer of the tile the next step consumes
+    // one pipeline step: tile jn (in LDS or arriving) -> acc_out, epilogue of acc_in (tile jn-1)
+    auto step = [&](int jn, const accvec<HG>& acc_in, accvec<HG>& acc_out) {
+      wait_tile(jn);
+      const u32x32 kv = kNBuf == 1 ? lds_read_tile(my) : lds_read_tile_raw(my_addr + buf * (kTileChunks * 16));
+      wait_lds();
+      if (jn + kNBuf < nj) dma(jn + kNBuf, buf);
+      buf = (buf + 1 == kNBuf) ? 0 : buf + 1;
+      acc_out = mfma_tile<HG>(f, kv);                       // tile jn on the matrix cores ...
+      finish(jn - 1, tile_epilogue<HG>(f, acc_in));         // ... tile jn-1 on the vector ALU
+    };
+    if (nj > 0) {
+#pragma unroll
+      for (int b = 0; b < kNBuf; ++b)
+        if (b < nj) dma(b, b);
+      wait_tile(0);
+      const u32x32 kv0 = kNBuf == 1 ? lds_read_tile(my) : lds_read_tile_raw(my_addr);
+      wait_lds();
+      if (kNBuf < nj) dma(kNBuf, 0);
+      buf = (kNBuf == 1) ? 0 : 1;
+      accvec<HG> acc_a = mfma_tile<HG>(f, kv0), acc_b;
+      int j = 0;                                            // acc_a holds tile j
+      for (; j + 2 < nj; j += 2) {
+        step(j + 1, acc_a, acc_b);
+        step(j + 2, acc_b, acc_a);
+      }
+      if (j + 1 < nj) {
+        step(j + 1, acc_a, acc_b);
+        finish(j + 1, tile_epilogue<HG>(f, acc_b));
+      } else {
+        finish(j, tile_epilogue<HG>(f, acc_a));
+      }
     }
-    row_next = (v + 4 < n_tiles) ? row_of(v + 4) : -1;
-#ifndef HISA_EXP_NO_FETCH
+  } else {
+    TileRegs<KDT> regs;
+    int row_next = nj > 0 ? __builtin_amdgcn_readfirstlane(row_of(wave)) : -1;
     if (row_next >= 0) tile_fetch_buf<KDT>(regs, krsrc, row_next * row_bytes, lane_offs);
-#endif
-    if (row0 >= 0) {
-      wave_lds_sync();
-      s = score_tile<HG>(f, my);
-      const int row = row0 + (lane & 31);
-      if (KDT == DT_FP8) s *= sbase[row];
-      if (row >= n_vis) s = neg_inf();
+    for (int v = wave; v < n_active; v += 4) {
+      const int row0 = row_next;
+      float s = neg_inf();
+      if (row0 >= 0) {
+        wave_lds_sync();
+        tile_store<KDT>(my, regs);
+      }
+      row_next = (v + 4 < n_active) ? __builtin_amdgcn_readfirstlane(row_of(v + 4)) : -1;
+      if (row_next >= 0) tile_fetch_buf<KDT>(regs, krsrc, row_next * row_bytes, lane_offs);
+      if (row0 >= 0) {
+        wave_lds_sync();
+        s = score_tile<HG>(f, my);
+        const int row = row0 + (lane & 31);
+        if (KDT == DT_FP8) s *= sbase[row];
+        if (row >= n_vis) s = neg_inf();
+      }
+      if (lane < 32) sc[v * 32 + lane] = s;
     }
-    if (lane < 32) sc[v * 32 + lane] = s;
   }
   __syncthreads();
+  const int n_cand_slots = n_active * 32;   // score slots actually written
 
   int32_t* oi = topk_idx + (long)t * k;
   float* os = topk_scores ? topk_scores + (long)t * k : nullptr;
@@ -517,11 +590,7 @@ __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int
     oi[p] = blk_ids[slot] * a.B + (i - slot * a.B);
     if (os) os[p] = key_to_score(key);
   };
-#ifdef HISA_EXP_SKIP_SELECT
-  if (threadIdx.x < 32) oi[threadIdx.x] = (int)sc[threadIdx.x * 7];
-  return;
-#endif
-  const int n_out = select_topk<256, E>(sm, n_slots, k, load, emit);
+  const int n_out = select_topk<256, E>(sm, n_cand_slots, k, load, emit);
   for (int p = n_out + threadIdx.x; p < k; p += 256) {
     oi[p] = -1;
     if (os) os[p] = neg_inf();
