@@ -6,6 +6,8 @@
 //    both the contiguous store and the MFMA-layout load are bank-conflict free.
 //  * select_topk: exact per-row top-k (Eqs. 2, 6, 9) by MSB-first radix select on order-preserving
 //    keys held in registers, ties to the lower index, output in ascending index order.
+//  * score_slot: the swizzled LDS position of a candidate's score, conflict-free both for the
+//    scoring waves (32 consecutive candidates) and for the selecting threads (E consecutive each).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -420,41 +422,91 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t mask) {
                                    __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
+// LDS word of candidate c in a score array: inside every row of 32 words, the eight 4-word
+// groups are permuted by the row number, so that 8 lanes reading 16 bytes from 8 consecutive
+// rows (one thread = one row in the select) hit 8 different bank groups.
+__device__ __forceinline__ int score_slot(int c) {
+  return (c & ~31) | ((((c >> 2) ^ (c >> 5)) & 7) << 2) | (c & 3);
+}
+
 template <int THREADS, int E>
 struct SelectSmem {
   static constexpr int NW = THREADS / 64;
+  static constexpr int CAP = 2048;   // entries of the threshold-bin list (fast path)
   uint32_t hist[256];
-  uint32_t tab_gt[E * NW];
-  uint32_t tab_eq[E * NW];
-  uint32_t red[3 * NW];
-  uint32_t bcast[2];
+  uint32_t red[4 * NW];
+  uint32_t bcast[4];
+  uint32_t n_list;
+  uint16_t list[CAP];
 };
 
+// Finds, in a 256-bin histogram of digit counts, the digit that holds the krem-th largest
+// element: counts above it < krem <= counts above it + its own.  Wave 0 only; publishes
+// bcast[0] = digit, bcast[1] = krem - (count above), bcast[2] = count in the digit's bin.
+__device__ __forceinline__ void find_digit(const uint32_t* hist, uint32_t* bcast, uint32_t krem,
+                                           int lane) {
+  const uint32_t c0 = hist[4 * lane + 0], c1 = hist[4 * lane + 1];
+  const uint32_t c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
+  const uint32_t s = c0 + c1 + c2 + c3;
+  uint32_t S = s;   // inclusive suffix sum over lanes
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t v = __shfl_down(S, off);
+    if (lane + off < 64) S += v;
+  }
+  const uint32_t a3 = S - s, a2 = a3 + c3, a1 = a2 + c2, a0 = a1 + c1;
+  int dsel = -1;
+  uint32_t above = 0, mine = 0;
+  if (a3 < krem && krem <= a3 + c3) { dsel = 3; above = a3; mine = c3; }
+  if (a2 < krem && krem <= a2 + c2) { dsel = 2; above = a2; mine = c2; }
+  if (a1 < krem && krem <= a1 + c1) { dsel = 1; above = a1; mine = c1; }
+  if (a0 < krem && krem <= a0 + c0) { dsel = 0; above = a0; mine = c0; }
+  if (dsel >= 0) {
+    bcast[0] = (uint32_t)(4 * lane + dsel);
+    bcast[1] = krem - above;
+    bcast[2] = mine;
+  }
+}
+
 // Exact top-k of one row by one workgroup of THREADS threads, n <= THREADS * E elements.
-//   load(i)  -> key of element i (0: not a candidate); element i is held by thread i % THREADS.
+//   load4(q) -> keys of elements 4q .. 4q+3 (0: not a candidate); load1(i) -> key of element i.
+//   Thread t holds the E consecutive elements t*E .. t*E+E-1 in registers.
 //   emit(pos, i, key): element i is the pos-th selected, in ascending i.
 // Returns the number selected: min(k, #candidates).  Order: key descending, then i ascending.
+// Method: MSB-first radix select on the bits below the candidates' common prefix.  The first
+// 8-bit pass histograms the registers; the few elements that fall into the threshold bin are
+// listed in LDS and the remaining passes run over that list only.  (If the bin overflows the
+// list -- many equal keys -- the passes keep running over the registers.)  Positions come from
+// one workgroup scan of per-thread counts: output is ascending, ties go to the lower index.
 // Every thread of the workgroup must call it (it contains workgroup barriers).
-template <int THREADS, int E, class Load, class Emit>
-__device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, int k, Load load,
-                                           Emit emit) {
+template <int THREADS, int E, class Load4, class Load1, class Emit>
+__device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, int k, Load4 load4,
+                                           Load1 load1, Emit emit) {
+  static_assert(E % 4 == 0, "elements per thread come in groups of four");
   constexpr int NW = THREADS / 64;
+  constexpr int CAP = SelectSmem<THREADS, E>::CAP;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
+  const int i0 = tid * E;
 
   typedef uint32_t keyvec __attribute__((ext_vector_type(E)));
-  keyvec key;   // one vector value, not an array: see the staging note above
+  keyvec key;   // one vector value, not an array (arrays that live across barriers go to scratch)
   uint32_t cnt = 0, k_and = 0xffffffffu, k_or = 0u;
 #pragma unroll
-  for (int j = 0; j < E; ++j) {
-    const int i = j * THREADS + tid;
-    const uint32_t kj = (i < n) ? load(i) : 0u;
-    key[j] = kj;
-    if (kj) {
-      ++cnt;
-      k_and &= kj;
-      k_or |= kj;
+  for (int g = 0; g < E / 4; ++g) {
+    uint4 q4 = make_uint4(0u, 0u, 0u, 0u);
+    if (i0 + 4 * g < n) q4 = load4((i0 >> 2) + g);
+    const uint32_t kk[4] = {q4.x, q4.y, q4.z, q4.w};
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const uint32_t kj = (i0 + 4 * g + x < n) ? kk[x] : 0u;
+      key[4 * g + x] = kj;
+      if (kj) {
+        ++cnt;
+        k_and &= kj;
+        k_or |= kj;
+      }
     }
   }
 #pragma unroll
@@ -468,6 +520,8 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
     sm.red[NW + wave] = k_and;
     sm.red[2 * NW + wave] = k_or;
   }
+  if (tid == 0) sm.n_list = 0u;
+  for (int b = tid; b < 256; b += THREADS) sm.hist[b] = 0u;
   __syncthreads();
   cnt = 0;
   k_and = 0xffffffffu;
@@ -487,41 +541,53 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
     int hi = diff ? 32 - __builtin_clz(diff) : 0;           // low bits that vary among candidates
     uint32_t pref = (hi >= 32) ? 0u : (k_or >> hi) << hi;   // bits above are common to all
     uint32_t krem = (uint32_t)k;
+    bool on_list = false;
+    uint32_t n_c = 0;
+    if (hi > 0) {
+      // first pass: every candidate shares the bits above hi, so all of them are counted
+      const int wbits = hi < 8 ? hi : 8;
+      const int shift = hi - wbits;
+      const uint32_t dmask = (1u << wbits) - 1u;
+#pragma unroll
+      for (int j = 0; j < E; ++j)
+        if (key[j]) atomicAdd(&sm.hist[(key[j] >> shift) & dmask], 1u);
+      __syncthreads();
+      if (wave == 0) find_digit(sm.hist, sm.bcast, krem, lane);
+      __syncthreads();
+      const uint32_t D = sm.bcast[0];
+      krem = sm.bcast[1];
+      n_c = sm.bcast[2];
+      pref |= D << shift;
+      hi = shift;
+      if (hi > 0 && n_c <= (uint32_t)CAP) {
+        on_list = true;
+#pragma unroll
+        for (int j = 0; j < E; ++j)
+          if (key[j] && ((key[j] >> shift) & dmask) == D)
+            sm.list[atomicAdd(&sm.n_list, 1u)] = (uint16_t)(i0 + j);
+      }
+    }
     while (hi > 0) {
       const int wbits = hi < 8 ? hi : 8;
       const int shift = hi - wbits;
       const uint32_t dmask = (1u << wbits) - 1u;
+      __syncthreads();   // list complete / previous digit read by everyone
       for (int b = tid; b < 256; b += THREADS) sm.hist[b] = 0u;
       __syncthreads();
+      if (on_list) {
+        for (uint32_t p = tid; p < n_c; p += THREADS) {
+          const uint32_t kj = load1((int)sm.list[p]);
+          if ((kj >> hi) == (pref >> hi)) atomicAdd(&sm.hist[(kj >> shift) & dmask], 1u);
+        }
+      } else {
 #pragma unroll
-      for (int j = 0; j < E; ++j) {
-        const uint32_t kj = key[j];
-        const bool in = kj && (hi >= 32 || (kj >> hi) == (pref >> hi));
-        if (in) atomicAdd(&sm.hist[(kj >> shift) & dmask], 1u);
+        for (int j = 0; j < E; ++j) {
+          const uint32_t kj = key[j];
+          if (kj && (kj >> hi) == (pref >> hi)) atomicAdd(&sm.hist[(kj >> shift) & dmask], 1u);
+        }
       }
       __syncthreads();
-      if (wave == 0) {
-        const uint32_t c0 = sm.hist[4 * lane + 0], c1 = sm.hist[4 * lane + 1];
-        const uint32_t c2 = sm.hist[4 * lane + 2], c3 = sm.hist[4 * lane + 3];
-        const uint32_t s = c0 + c1 + c2 + c3;
-        uint32_t S = s;   // inclusive suffix sum over lanes
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-          const uint32_t v = __shfl_down(S, off);
-          if (lane + off < 64) S += v;
-        }
-        const uint32_t a3 = S - s, a2 = a3 + c3, a1 = a2 + c2, a0 = a1 + c1;
-        int dsel = -1;
-        uint32_t above = 0;
-        if (a3 < krem && krem <= a3 + c3) { dsel = 3; above = a3; }
-        if (a2 < krem && krem <= a2 + c2) { dsel = 2; above = a2; }
-        if (a1 < krem && krem <= a1 + c1) { dsel = 1; above = a1; }
-        if (a0 < krem && krem <= a0 + c0) { dsel = 0; above = a0; }
-        if (dsel >= 0) {
-          sm.bcast[0] = (uint32_t)(4 * lane + dsel);
-          sm.bcast[1] = krem - above;
-        }
-      }
+      if (wave == 0) find_digit(sm.hist, sm.bcast, krem, lane);
       __syncthreads();
       pref |= sm.bcast[0] << shift;
       krem = sm.bcast[1];
@@ -531,65 +597,44 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
     r = krem;
   }
 
-  // Ranks in index order.  Element i = j*THREADS + wave*64 + lane, so (j, wave, lane) ascending
-  // is i ascending: count per (j, wave), exclusive-scan the table, add the in-wave rank.
+  // Positions in index order: thread t's elements precede thread t+1's, so an exclusive scan of
+  // the per-thread counts (selected-for-sure, equal-to-threshold) gives every thread its base.
+  uint32_t g_cnt = 0, e_cnt = 0;
 #pragma unroll
   for (int j = 0; j < E; ++j) {
-    const uint64_t bg = __ballot(key[j] > tau);
-    const uint64_t be = __ballot(tau != 0u && key[j] == tau);
-    if (lane == 0) {
-      sm.tab_gt[j * NW + wave] = __popcll(bg);
-      sm.tab_eq[j * NW + wave] = __popcll(be);
+    g_cnt += key[j] > tau;
+    e_cnt += (tau != 0u && key[j] == tau);
+  }
+  uint32_t g_inc = g_cnt, e_inc = e_cnt;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t vg = __shfl_up(g_inc, off), ve = __shfl_up(e_inc, off);
+    if (lane >= off) {
+      g_inc += vg;
+      e_inc += ve;
     }
   }
-  __syncthreads();
-  if (wave == 0) {
-    constexpr int NT = E * NW;
-    constexpr int PER = (NT + 63) / 64;
-    uint32_t sg = 0, se = 0;
-#pragma unroll
-    for (int x = 0; x < PER; ++x) {
-      const int e = lane * PER + x;
-      if (e < NT) {
-        sg += sm.tab_gt[e];
-        se += sm.tab_eq[e];
-      }
-    }
-    uint32_t Sg = sg, Se = se;   // inclusive prefix over lanes
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t vg = __shfl_up(Sg, off), ve = __shfl_up(Se, off);
-      if (lane >= off) {
-        Sg += vg;
-        Se += ve;
-      }
-    }
-    uint32_t rg = Sg - sg, re = Se - se;
-#pragma unroll
-    for (int x = 0; x < PER; ++x) {
-      const int e = lane * PER + x;
-      if (e < NT) {
-        const uint32_t tg = sm.tab_gt[e], te = sm.tab_eq[e];
-        sm.tab_gt[e] = rg;
-        sm.tab_eq[e] = re;
-        rg += tg;
-        re += te;
-      }
-    }
+  __syncthreads();   // sm.red is free again
+  if (lane == 63) {
+    sm.red[wave] = g_inc;
+    sm.red[NW + wave] = e_inc;
   }
   __syncthreads();
+  uint32_t g_run = g_inc - g_cnt, e_run = e_inc - e_cnt;
+#pragma unroll
+  for (int v = 0; v < NW; ++v) {
+    if (v < wave) {
+      g_run += sm.red[v];
+      e_run += sm.red[NW + v];
+    }
+  }
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     const bool gt = key[j] > tau;
     const bool eq = tau != 0u && key[j] == tau;
-    const uint64_t bg = __ballot(gt);
-    const uint64_t be = __ballot(eq);
-    const uint32_t rank_gt = sm.tab_gt[j * NW + wave] + lanes_below(bg);
-    const uint32_t rank_eq = sm.tab_eq[j * NW + wave] + lanes_below(be);
-    if (gt || (eq && rank_eq < r)) {
-      const uint32_t pos = rank_gt + (rank_eq < r ? rank_eq : r);
-      emit((int)pos, j * THREADS + tid, key[j]);
-    }
+    if (gt || (eq && e_run < r)) emit((int)(g_run + (e_run < r ? e_run : r)), i0 + j, key[j]);
+    g_run += gt;
+    e_run += eq;
   }
   return n_valid < k ? n_valid : k;
 }

@@ -413,10 +413,25 @@ __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
   int32_t* oi = a.out_idx + orow * a.k;
   float* os = a.out_scores ? a.out_scores + orow * a.k : nullptr;
   const int n_last = n - 1;
-  auto load = [&](int i) -> uint32_t {
+  const float* rowp = sc + base;
+  const bool vec_ok = (reinterpret_cast<uintptr_t>(rowp) & 15) == 0;
+  auto key_of = [&](int i, float v) -> uint32_t {
     if (MAP == MAP_BLOCKS && (i == 0 || i == n_last)) return 0xffffffffu;   // forced blocks
-    return ordered_key(sc[base + i]);
+    return ordered_key(v);
   };
+  auto load4 = [&](int q) -> uint4 {
+    const int i = 4 * q;
+    float v[4];
+    if (vec_ok && i + 3 < n) {
+      const float4 f = *reinterpret_cast<const float4*>(rowp + i);
+      v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
+    } else {
+#pragma unroll
+      for (int x = 0; x < 4; ++x) v[x] = (i + x < n) ? rowp[i + x] : neg_inf();
+    }
+    return make_uint4(key_of(i, v[0]), key_of(i + 1, v[1]), key_of(i + 2, v[2]), key_of(i + 3, v[3]));
+  };
+  auto load1 = [&](int i) -> uint32_t { return key_of(i, rowp[i]); };
   auto emit = [&](int p, int i, uint32_t key) {
     int id;
     if (MAP == MAP_CAND) {
@@ -430,7 +445,7 @@ __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
     oi[p] = id;
     if (os) os[p] = key_to_score(key);
   };
-  const int n_out = select_topk<THREADS, E>(sm, n, a.k, load, emit);
+  const int n_out = select_topk<THREADS, E>(sm, n, a.k, load4, load1, emit);
   for (int p = n_out + threadIdx.x; p < a.k; p += THREADS) {
     oi[p] = -1;
     if (os) os[p] = neg_inf();
@@ -514,7 +529,7 @@ __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int
       const int r = row_at(j);
       const int row = (r < 0 ? 0 : r) + (lane & 31);
       if (row >= (r < 0 ? 0 : n_vis)) s = neg_inf();
-      if (lane < 32) sc[(wave + 4 * j) * 32 + lane] = s;
+      if (lane < 32) sc[score_slot((wave + 4 * j) * 32 + lane)] = s;
     };
     // the DMA of tile j is complete once at most 8 * (tiles issued after it) loads are pending
     auto wait_tile = [&](int j) {
@@ -576,7 +591,7 @@ __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int
         if (KDT == DT_FP8) s *= sbase[row];
         if (row >= n_vis) s = neg_inf();
       }
-      if (lane < 32) sc[v * 32 + lane] = s;
+      if (lane < 32) sc[score_slot(v * 32 + lane)] = s;
     }
   }
   __syncthreads();
@@ -584,13 +599,17 @@ __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int
 
   int32_t* oi = topk_idx + (long)t * k;
   float* os = topk_scores ? topk_scores + (long)t * k : nullptr;
-  auto load = [&](int i) -> uint32_t { return ordered_key(sc[i]); };
+  auto load4 = [&](int q) -> uint4 {
+    const float4 v = *reinterpret_cast<const float4*>(sc + score_slot(4 * q));
+    return make_uint4(ordered_key(v.x), ordered_key(v.y), ordered_key(v.z), ordered_key(v.w));
+  };
+  auto load1 = [&](int i) -> uint32_t { return ordered_key(sc[score_slot(i)]); };
   auto emit = [&](int p, int i, uint32_t key) {
     const int slot = i / a.B;
     oi[p] = blk_ids[slot] * a.B + (i - slot * a.B);
     if (os) os[p] = key_to_score(key);
   };
-  const int n_out = select_topk<256, E>(sm, n_cand_slots, k, load, emit);
+  const int n_out = select_topk<256, E>(sm, n_cand_slots, k, load4, load1, emit);
   for (int p = n_out + threadIdx.x; p < k; p += 256) {
     oi[p] = -1;
     if (os) os[p] = neg_inf();
