@@ -160,7 +160,7 @@ SelectArgs select_base(const hisa_queries* q, const hisa_keys* k) {
 template <int HG, int KDT, int E>
 int launch_fused_hg(const ScoreArgs& a, int k, int32_t* topk_idx, float* topk_scores,
                     hipStream_t st) {
-  const size_t sh = (size_t)4 * kNBuf * kTileChunks * 16 + (size_t)a.m * a.B * 4 +
+  const size_t sh = (size_t)4 * kNBuf * TileGeom<KDT>::kBufBytes + (size_t)a.m * a.B * 4 +
                     sizeof(SelectSmem<256, E>) +
                     (size_t)a.m * 4 + 16;
   auto kern = k_refine_fused<HG, KDT, E>;

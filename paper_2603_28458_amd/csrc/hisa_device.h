@@ -370,6 +370,73 @@ __device__ __forceinline__ void tile_dma_bf16(__amdgpu_buffer_rsrc_t rsrc, uint3
                                          (int)o[i], tile_byte_off, 0, 0);
 }
 
+// fp8 keys by DMA: the 4 KB of a tile as 256 chunks of 16 codes; LDS chunk p = i*64 + lane holds
+// global chunk (row r = p / 8, column (p % 8) xor (r % 8)), so the 8-byte MFMA-layout reads
+// below spread over the banks.  A fifth transfer brings the 32 per-token scales (as 64 floats).
+__device__ __forceinline__ void tile_dma_fp8(__amdgpu_buffer_rsrc_t rsrc, __amdgpu_buffer_rsrc_t srsrc,
+                                             uint32_t lds_addr, int row0) {
+  const int lane = lane_id();
+  const int voff = (lane >> 3) * 128 + (((lane & 7) ^ (lane >> 3)) << 4);
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(uintptr_t)(lds_addr + i * 1024), 16, voff,
+                                             row0 * 128 + i * 1024, 0, 0);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(srsrc, (lds_void*)(uintptr_t)(lds_addr + 4096), 4, lane * 4,
+                                           row0 * 4, 0, 0);
+}
+
+// B operands of an fp8 tile staged by tile_dma_fp8: eight 8-byte reads per lane (raw
+// instructions, see lds_read_tile_raw), widened exactly to bf16.  The data is complete on return.
+typedef uint32_t u32x2e __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ u32x32 lds_read_tile_fp8_raw(uint32_t tile_addr) {
+  const int lane = lane_id();
+  const int half = lane >> 5;
+  const int r = lane & 31;
+  uint32_t ad[8];
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk)
+    ad[kk] = tile_addr + (uint32_t)(r * 128 + ((kk ^ (r & 7)) << 4) + half * 8);
+  u32x2e x0, x1, x2, x3, x4, x5, x6, x7;
+  asm volatile(
+      "ds_read_b64 %0, %8\n\t"
+      "ds_read_b64 %1, %9\n\t"
+      "ds_read_b64 %2, %10\n\t"
+      "ds_read_b64 %3, %11\n\t"
+      "ds_read_b64 %4, %12\n\t"
+      "ds_read_b64 %5, %13\n\t"
+      "ds_read_b64 %6, %14\n\t"
+      "ds_read_b64 %7, %15\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(x0), "=&v"(x1), "=&v"(x2), "=&v"(x3), "=&v"(x4), "=&v"(x5), "=&v"(x6), "=&v"(x7)
+      : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3]), "v"(ad[4]), "v"(ad[5]), "v"(ad[6]), "v"(ad[7])
+      : "memory");
+  const u32x2e xs[8] = {x0, x1, x2, x3, x4, x5, x6, x7};
+  u32x32 kv;
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    const uint2 lo = fp8x4_to_bf16x4(xs[kk][0]), hi = fp8x4_to_bf16x4(xs[kk][1]);
+    kv[4 * kk + 0] = lo.x;
+    kv[4 * kk + 1] = lo.y;
+    kv[4 * kk + 2] = hi.x;
+    kv[4 * kk + 3] = hi.y;
+  }
+  return kv;
+}
+
+// One float from LDS by raw instruction (same reason), complete on return.
+__device__ __forceinline__ float lds_read_f32_raw(uint32_t addr) {
+  float v;
+  asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(addr) : "memory");
+  return v;
+}
+
+// Wait until at most N global loads of this wave are outstanding (loads complete in order).
+template <int N>
+__device__ __forceinline__ void wait_vmem_le() {
+  __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+}
+
 // Wait until every outstanding global load (vmcnt) / LDS access (lgkmcnt) of this wave is done.
 __device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0f70); }
 __device__ __forceinline__ void wait_lds() { __builtin_amdgcn_s_waitcnt(0xc07f); }

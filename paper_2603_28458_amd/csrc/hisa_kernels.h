@@ -236,14 +236,116 @@ __device__ __forceinline__ TileLoc tile_loc(const ScoreArgs& a, int t, int v, bo
   return L;
 }
 
+// ------------------------------------------------------------------------------------------
+// The per-wave scoring pipeline shared by Stage 2 and the per-query scoring kernels.
+//
+// A wave owns one query (QFrag in registers) and a ring of NB LDS tiles.  For its j-th tile it
+//   * DMAs the key rows global -> LDS NB tiles ahead (no registers involved),
+//   * copies the staged tile into registers as MFMA B operands (which frees the LDS tile),
+//   * runs the 16 MFMAs of tile j while the vector ALU does the ReLU / gate / head-sum epilogue of
+//     tile j-1 (two accumulator sets swap roles, the loop is unrolled by two).
+// row_at(j): first key row of tile j (wave-uniform, a row inside the sequence's key array);
+// finish(j, s): lane l < 32 receives the score of key row_at(j) + l (fp8: already scaled).
+template <int KDT>
+struct TileGeom {
+  static constexpr int kLoads = KDT == DT_BF16 ? 8 : 5;                 // DMA instructions per tile
+  static constexpr int kBufBytes = KDT == DT_BF16 ? 8192 : 4096 + 256;  // LDS per staged tile
+};
+
+template <int HG, int KDT, int NB, class RowAt, class Finish>
+__device__ __forceinline__ void wave_pipeline(const QFrag<HG>& f, __amdgpu_buffer_rsrc_t krsrc,
+                                              __amdgpu_buffer_rsrc_t srsrc, uint32_t ring_addr, int nj,
+                                              RowAt row_at, Finish finish) {
+  static_assert(NB >= 1 && NB <= 3, "ring of one to three tiles");
+  constexpr int L = TileGeom<KDT>::kLoads;
+  constexpr int BB = TileGeom<KDT>::kBufBytes;
+  const int lane = lane_id();
+  const u32x8 lane_offs = tile_lane_offsets_bf16();
+  auto dma = [&](int j, int buf) {
+    const int r = row_at(j);
+    if constexpr (KDT == DT_BF16)
+      tile_dma_bf16(krsrc, ring_addr + buf * BB, r * (kD * 2), lane_offs);
+    else
+      tile_dma_fp8(krsrc, srsrc, ring_addr + buf * BB, r);
+  };
+  // the DMA of tile j is complete once at most L * (tiles issued after it) loads are pending
+  auto wait_tile = [&](int j) {
+    const int later = (nj - 1 - j) < (NB - 1) ? (nj - 1 - j) : (NB - 1);
+    if (later >= 2) wait_vmem_le<2 * L>();
+    else if (later == 1) wait_vmem_le<L>();
+    else wait_vmem_le<0>();
+  };
+  auto read_tile = [&](int buf, float& scale) -> u32x32 {
+    const uint32_t addr = ring_addr + buf * BB;
+    if constexpr (KDT == DT_BF16) {
+      scale = 1.f;
+      return lds_read_tile_raw(addr);
+    } else {
+      scale = lds_read_f32_raw(addr + 4096 + (lane & 31) * 4);
+      return lds_read_tile_fp8_raw(addr);
+    }
+  };
+  if (nj <= 0) return;
+#pragma unroll
+  for (int b = 0; b < NB; ++b)
+    if (b < nj) dma(b, b);
+  int buf = 0;                       // ring slot of the tile the next step consumes
+  float sc_a = 1.f, sc_b = 1.f;      // fp8: per-key scales of the tiles held in acc_a / acc_b
+  // one step: tile jn -> acc_out (matrix cores) while tile jn-1 = acc_in is finished (vector ALU)
+  auto step = [&](int jn, const accvec<HG>& acc_in, float sc_in, accvec<HG>& acc_out, float& sc_out) {
+    wait_tile(jn);
+    const u32x32 kv = read_tile(buf, sc_out);
+    if (jn + NB < nj) dma(jn + NB, buf);
+    buf = (buf + 1 == NB) ? 0 : buf + 1;
+    acc_out = mfma_tile<HG>(f, kv);
+    finish(jn - 1, tile_epilogue<HG>(f, acc_in) * sc_in);
+  };
+  wait_tile(0);
+  const u32x32 kv0 = read_tile(0, sc_a);
+  if (NB < nj) dma(NB, 0);
+  buf = (NB == 1) ? 0 : 1;
+  accvec<HG> acc_a = mfma_tile<HG>(f, kv0), acc_b;
+  int j = 0;                         // acc_a holds tile j
+  for (; j + 2 < nj; j += 2) {
+    step(j + 1, acc_a, sc_a, acc_b, sc_b);
+    step(j + 2, acc_b, sc_b, acc_a, sc_a);
+  }
+  if (j + 1 < nj) {
+    step(j + 1, acc_a, sc_a, acc_b, sc_b);
+    finish(j + 1, tile_epilogue<HG>(f, acc_b) * sc_b);
+  } else {
+    finish(j, tile_epilogue<HG>(f, acc_a) * sc_a);
+  }
+}
+
+// Key array of one sequence as buffer descriptors (rows, and per-token scales for fp8).
+template <int KDT>
+__device__ __forceinline__ void key_buffers(const ScoreArgs& a, int seq, __amdgpu_buffer_rsrc_t& krsrc,
+                                            __amdgpu_buffer_rsrc_t& srsrc) {
+  const int rb = KDT == DT_BF16 ? 2 : 1;
+  krsrc = key_buffer((const char*)a.keys + (long)seq * a.rows_per_seq * kD * rb, a.rows_per_seq * kD * rb);
+  srsrc = key_buffer(a.k_scale ? (const void*)(a.k_scale + (long)seq * a.rows_per_seq) : a.keys,
+                     a.k_scale ? a.rows_per_seq * 4 : 0);
+}
+
+// Lane j of the returned pair holds rows[j] / rows[64 + j]; at(j) broadcasts entry j.
+struct LaneTable {
+  int lo, hi;
+  __device__ __forceinline__ int at(int j) const {
+    return j < 64 ? __builtin_amdgcn_readlane(lo, j) : __builtin_amdgcn_readlane(hi, j - 64);
+  }
+};
+
 // Eq. 1 / Eq. 5 / Eq. 8 on MFMA for arbitrary queries: one workgroup of 4 waves per (group of
-// tiles, query); each wave stages its own tiles (nothing is shared between queries here: this is
-// the decode / two-kernel path).  Writes scores, and -inf for masked slots in gather mode.
+// tiles, query); each wave runs the scoring pipeline over its own tiles (nothing is shared between
+// queries here: this is the decode / two-kernel path).  Writes scores, and -inf for masked slots
+// in gather mode.  tiles_per_wave <= 64.
 template <int HG, int KDT>
-__global__ __launch_bounds__(256) void k_score_ranges(ScoreArgs a) {
-  __shared__ uint4 stage[4][kTileChunks];
+__global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
+  constexpr int NB = 2;
+  __shared__ __align__(16) unsigned char ring[4 * NB * TileGeom<KDT>::kBufBytes];
   const int t = a.t_begin + blockIdx.y;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   int seq;
   const int pos = query_pos(a, t, seq);
   const bool gather = a.block_idx != nullptr;
@@ -252,32 +354,55 @@ __global__ __launch_bounds__(256) void k_score_ranges(ScoreArgs a) {
   const int v0 = blockIdx.x * 4 * a.tiles_per_wave;
   if (v0 >= n_tiles) return;
   float* out = a.out + (long)blockIdx.y * a.ld;
-  const int rb = KDT == DT_BF16 ? 2 : 1;
-  const char* kbase = (const char*)a.keys + (long)seq * a.rows_per_seq * kD * rb;
-  const float* sbase = a.k_scale ? a.k_scale + (long)seq * a.rows_per_seq : nullptr;
+  const int n_blocks = (int)(a.rows_per_seq / a.B);
 
   QFrag<HG> f;
   load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
 
-  qfrag_ready<HG>(f);
-  TileRegs<KDT> regs;
-  for (int i = 0; i < a.tiles_per_wave; ++i) {
-    const int v = v0 + wave + 4 * i;
-    if (v >= n_tiles) break;
-    const TileLoc L = tile_loc(a, t, v, gather);
-    float s = neg_inf();
-    if (L.row0 >= 0 && L.row0 < n_vis) {
-      tile_fetch<KDT>(regs, kbase, L.row0, a.rows_per_seq);
-      wave_lds_sync();
-      tile_store<KDT>(stage[wave], regs);
-      wave_lds_sync();
-      s = score_tile<HG>(f, stage[wave]);
-      const long row = L.row0 + (lane & 31);
-      if (KDT == DT_FP8) s *= sbase[row < a.rows_per_seq ? row : a.rows_per_seq - 1];
-      if (row >= n_vis) s = neg_inf();
+  // this wave's tiles: v = v0 + wave + 4 i; lane i looks its tile up; tiles without a visible key
+  // are filled with -inf here (gather mode) and left out of the pipeline
+  int my_row = -1, my_out = 0;
+  {
+    const int v = v0 + wave + 4 * lane;
+    if (lane < a.tiles_per_wave && v < n_tiles) {
+      const TileLoc Lc = tile_loc(a, t, v, gather);
+      my_out = (int)Lc.out0;
+      const bool ok = Lc.row0 >= 0 && Lc.row0 < n_vis && (!gather || Lc.row0 / a.B < n_blocks);
+      if (ok) my_row = (int)Lc.row0;
+      else if (gather)
+        for (int x = 0; x < 32; ++x) out[my_out + x] = neg_inf();
     }
-    if (lane < 32 && (gather || L.row0 + lane < n_vis)) out[L.out0 + lane] = s;
   }
+  // compact the valid tiles to the low lanes (order does not matter)
+  const uint64_t okmask = __ballot(my_row >= 0);
+  const int nj = __popcll(okmask);
+  const int dst = (int)lanes_below(okmask);
+  LaneTable rows{-1, -1}, outs{0, 0};
+  {
+    // lane j fetches the j-th valid entry: the source lane is the j-th set bit of okmask
+    int src = 0;
+    uint64_t mrem = okmask;
+    for (int q = 0; q < 64; ++q) {           // wave-uniform loop over set bits
+      if (!mrem) break;
+      const int bit = __builtin_ctzll(mrem);
+      mrem &= mrem - 1;
+      if (lane == q) src = bit;
+    }
+    (void)dst;
+    rows.lo = __shfl(my_row, src);
+    outs.lo = __shfl(my_out, src);
+  }
+  qfrag_ready<HG>(f);
+  __amdgpu_buffer_rsrc_t krsrc, srsrc;
+  key_buffers<KDT>(a, seq, krsrc, srsrc);
+  const uint32_t ring_addr = lds_address(ring) + wave * NB * TileGeom<KDT>::kBufBytes;
+  wave_pipeline<HG, KDT, NB>(
+      f, krsrc, srsrc, ring_addr, nj, [&](int j) { return rows.at(j); },
+      [&](int j, float s) {
+        const int row = rows.at(j) + (lane & 31);
+        if (row >= n_vis) s = neg_inf();
+        if (lane < 32 && (gather || row < n_vis)) out[outs.at(j) + lane] = s;
+      });
 }
 
 // Eq. 1 / Eq. 5 on MFMA for a causal prefill of ONE sequence with consecutive positions: one
@@ -459,9 +584,9 @@ template <int HG, int KDT, int E>
 __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int32_t* topk_idx,
                                                          float* topk_scores) {
   extern __shared__ __align__(16) unsigned char smem[];
-  uint4* stage = reinterpret_cast<uint4*>(smem);                       // 4 x 8 KB
-  constexpr size_t kStageBytes = (size_t)4 * kNBuf * kTileChunks * 16;
-  float* sc = reinterpret_cast<float*>(smem + kStageBytes);   // m*B scores
+  constexpr int NB = kNBuf;
+  constexpr size_t kStageBytes = (size_t)4 * NB * TileGeom<KDT>::kBufBytes;
+  float* sc = reinterpret_cast<float*>(smem + kStageBytes);   // m*B scores (swizzled: score_slot)
   const int n_slots = a.m * a.B;
   SelectSmem<256, E>& sm =
       *reinterpret_cast<SelectSmem<256, E>*>(smem + kStageBytes + (size_t)n_slots * 4);
@@ -473,9 +598,6 @@ __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int
   int seq;
   const int pos = query_pos(a, t, seq);
   const int n_vis = pos + 1;
-  const int rb = KDT == DT_BF16 ? 2 : 1;
-  const char* kbase = (const char*)a.keys + (long)seq * a.rows_per_seq * kD * rb;
-  const float* sbase = a.k_scale ? a.k_scale + (long)seq * a.rows_per_seq : nullptr;
 
   QFrag<HG> f;
   load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
@@ -494,106 +616,33 @@ __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int
   __syncthreads();
   const int n_active = __builtin_amdgcn_readfirstlane(*n_used_p) * tpb;
   qfrag_ready<HG>(f);
-  // first key row of tile v, or -1 if its slot is empty / out of range / not visible (wave-uniform)
+  // first key row of tile v, or -1 if its slot is empty / out of range / not visible
   auto row_of = [&](int v) -> int {
     const int slot = v / tpb;
     const int blk = blk_ids[slot];
     const int row0 = blk * a.B + (v - slot * tpb) * 32;
     return (blk < 0 || blk >= n_blocks || row0 >= n_vis) ? -1 : row0;
   };
-  const int row_bytes = kD * rb;
-  const u32x8 lane_offs = tile_lane_offsets_bf16();
-  const __amdgpu_buffer_rsrc_t krsrc = key_buffer(kbase, a.rows_per_seq * row_bytes);
-  uint4* my = stage + wave * kNBuf * kTileChunks;
   const int nj = n_active > wave ? (n_active - wave + 3) >> 2 : 0;   // tiles of this wave
-
-  if constexpr (KDT == DT_BF16) {
-    // Software pipeline inside the wave: while the MFMAs of tile j+1 run, the ReLU / gate /
-    // head-sum epilogue of tile j executes on the vector ALU and the key rows of tile j+2 travel
-    // global -> LDS.  One 8 KB LDS tile per wave suffices: its rows are copied into registers
-    // (B operands) before the next DMA is issued.  The loop is unrolled by two so that the two
-    // accumulator sets swap roles without being copied.
-    const uint32_t my_addr = lds_address(my);
-    // first key row of this wave's j-th tile: lane j (of two registers) holds it
-    const int rows_lo = row_of(wave + 4 * (lane < nj ? lane : 0));
-    const int rows_hi = (nj > 64) ? row_of(wave + 4 * (lane + 64 < nj ? lane + 64 : 0)) : -1;
-    auto row_at = [&](int j) -> int {
-      return j < 64 ? __builtin_amdgcn_readlane(rows_lo, j) : __builtin_amdgcn_readlane(rows_hi, j - 64);
-    };
-    // tile j lives in (and is DMA'd into) LDS buffer j % kNBuf of this wave
-    auto dma = [&](int j, int buf) {
-      const int r = row_at(j);
-      tile_dma_bf16(krsrc, my_addr + buf * (kTileChunks * 16), (r < 0 ? 0 : r) * row_bytes, lane_offs);
-    };
-    auto finish = [&](int j, float s) {
-      const int r = row_at(j);
-      const int row = (r < 0 ? 0 : r) + (lane & 31);
-      if (row >= (r < 0 ? 0 : n_vis)) s = neg_inf();
-      if (lane < 32) sc[score_slot((wave + 4 * j) * 32 + lane)] = s;
-    };
-    // the DMA of tile j is complete once at most 8 * (tiles issued after it) loads are pending
-    auto wait_tile = [&](int j) {
-      const int later = (nj - 1 - j) < (kNBuf - 1) ? (nj - 1 - j) : (kNBuf - 1);
-      if (later >= 2) __builtin_amdgcn_s_waitcnt(0x4f70);        // vmcnt(16)
-      else if (later == 1) __builtin_amdgcn_s_waitcnt(0x0f78);   // vmcnt(8)
-      else wait_vmem();
-    };
-    int buf = 0;   // buffer of the tile the next step consumes
-    // one pipeline step: tile jn (in LDS or arriving) -> acc_out, epilogue of acc_in (tile jn-1)
-    auto step = [&](int jn, const accvec<HG>& acc_in, accvec<HG>& acc_out) {
-      wait_tile(jn);
-      const u32x32 kv = kNBuf == 1 ? lds_read_tile(my) : lds_read_tile_raw(my_addr + buf * (kTileChunks * 16));
-      wait_lds();
-      if (jn + kNBuf < nj) dma(jn + kNBuf, buf);
-      buf = (buf + 1 == kNBuf) ? 0 : buf + 1;
-      acc_out = mfma_tile<HG>(f, kv);                       // tile jn on the matrix cores ...
-      finish(jn - 1, tile_epilogue<HG>(f, acc_in));         // ... tile jn-1 on the vector ALU
-    };
-    if (nj > 0) {
-#pragma unroll
-      for (int b = 0; b < kNBuf; ++b)
-        if (b < nj) dma(b, b);
-      wait_tile(0);
-      const u32x32 kv0 = kNBuf == 1 ? lds_read_tile(my) : lds_read_tile_raw(my_addr);
-      wait_lds();
-      if (kNBuf < nj) dma(kNBuf, 0);
-      buf = (kNBuf == 1) ? 0 : 1;
-      accvec<HG> acc_a = mfma_tile<HG>(f, kv0), acc_b;
-      int j = 0;                                            // acc_a holds tile j
-      for (; j + 2 < nj; j += 2) {
-        step(j + 1, acc_a, acc_b);
-        step(j + 2, acc_b, acc_a);
-      }
-      if (j + 1 < nj) {
-        step(j + 1, acc_a, acc_b);
-        finish(j + 1, tile_epilogue<HG>(f, acc_b));
-      } else {
-        finish(j, tile_epilogue<HG>(f, acc_a));
-      }
-    }
-  } else {
-    TileRegs<KDT> regs;
-    int row_next = nj > 0 ? __builtin_amdgcn_readfirstlane(row_of(wave)) : -1;
-    if (row_next >= 0) tile_fetch_buf<KDT>(regs, krsrc, row_next * row_bytes, lane_offs);
-    for (int v = wave; v < n_active; v += 4) {
-      const int row0 = row_next;
-      float s = neg_inf();
-      if (row0 >= 0) {
-        wave_lds_sync();
-        tile_store<KDT>(my, regs);
-      }
-      row_next = (v + 4 < n_active) ? __builtin_amdgcn_readfirstlane(row_of(v + 4)) : -1;
-      if (row_next >= 0) tile_fetch_buf<KDT>(regs, krsrc, row_next * row_bytes, lane_offs);
-      if (row0 >= 0) {
-        wave_lds_sync();
-        s = score_tile<HG>(f, my);
-        const int row = row0 + (lane & 31);
-        if (KDT == DT_FP8) s *= sbase[row];
-        if (row >= n_vis) s = neg_inf();
-      }
-      if (lane < 32) sc[score_slot(v * 32 + lane)] = s;
-    }
-  }
+  // lane j holds the first key row of this wave's j-th tile (wave + 4j)
+  LaneTable rows;
+  rows.lo = row_of(wave + 4 * (lane < nj ? lane : 0));
+  rows.hi = (nj > 64) ? row_of(wave + 4 * (lane + 64 < nj ? lane + 64 : 0)) : -1;
+  __amdgpu_buffer_rsrc_t krsrc, srsrc;
+  key_buffers<KDT>(a, seq, krsrc, srsrc);
+  const uint32_t ring_addr = lds_address(smem) + wave * NB * TileGeom<KDT>::kBufBytes;
+  wave_pipeline<HG, KDT, NB>(
+      f, krsrc, srsrc, ring_addr, nj,
+      [&](int j) {
+        const int r = rows.at(j);
+        return r < 0 ? 0 : r;   // a tile without visible keys still flows through, masked below
+      },
+      [&](int j, float s) {
+        const int r = rows.at(j);
+        const int row = (r < 0 ? 0 : r) + (lane & 31);
+        if (row >= (r < 0 ? 0 : n_vis)) s = neg_inf();
+        if (lane < 32) sc[score_slot((wave + 4 * j) * 32 + lane)] = s;
+      });
   __syncthreads();
   const int n_cand_slots = n_active * 32;   // score slots actually written
 
