@@ -157,25 +157,27 @@ SelectArgs select_base(const hisa_queries* q, const hisa_keys* k) {
   return s;
 }
 
-template <int HG, int KDT, int E>
+// Fused Stage 2: kFusedWaves waves per query; EC = candidates per thread of a 256-thread select
+// (32: up to 8192 candidates, 64: up to 16384); with 8 waves the per-thread count halves.
+template <int HG, int KDT, int EC>
 int launch_fused_hg(const ScoreArgs& a, int k, int32_t* topk_idx, float* topk_scores,
                     hipStream_t st) {
-  const size_t sh = (size_t)4 * kNBuf * TileGeom<KDT>::kBufBytes + (size_t)a.m * a.B * 4 +
-                    sizeof(SelectSmem<256, E>) +
-                    (size_t)a.m * 4 + 16;
-  auto kern = k_refine_fused<HG, KDT, E>;
+  constexpr int NW = kFusedWaves;
+  constexpr int E = ((EC * 4 + NW - 1) / NW + 3) / 4 * 4;
+  const size_t sh = (size_t)NW * kNBuf * TileGeom<KDT>::kBufBytes + (size_t)a.m * a.B * 4;
+  auto kern = k_refine_fused<HG, KDT, NW, kNBuf, E>;
   // more than 64 KB of LDS per workgroup has to be asked for explicitly
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh) != hipSuccess)
     return HISA_ERR_LAUNCH;
-  hipLaunchKernelGGL(kern, dim3(a.t_count), dim3(256), sh, st, a, k, topk_idx, topk_scores);
+  hipLaunchKernelGGL(kern, dim3(a.t_count), dim3(NW * 64), sh, st, a, k, topk_idx, topk_scores);
   return HISA_OK;
 }
 
-template <int KDT, int E>
+template <int KDT, int EC>
 int launch_fused(const ScoreArgs& a, int k, int32_t* topk_idx, float* topk_scores, hipStream_t st) {
-  return a.H == 64 ? launch_fused_hg<2, KDT, E>(a, k, topk_idx, topk_scores, st)
-                   : launch_fused_hg<1, KDT, E>(a, k, topk_idx, topk_scores, st);
+  return a.H == 64 ? launch_fused_hg<2, KDT, EC>(a, k, topk_idx, topk_scores, st)
+                   : launch_fused_hg<1, KDT, EC>(a, k, topk_idx, topk_scores, st);
 }
 
 // Flat indexer: rows of queries scored per chunk, and the size of the segment-merge area.

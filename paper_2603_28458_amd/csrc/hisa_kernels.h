@@ -6,13 +6,15 @@
 
 #include "hisa_device.h"
 
-#ifndef HISA_NBUF
-#define HISA_NBUF 1
-#endif
 
 namespace hisa {
 
-constexpr int kNBuf = HISA_NBUF;   // LDS tiles per wave in the fused Stage 2 kernel (DMA look-ahead)
+// Fused Stage 2 kernel: waves per query and LDS tiles per wave.  Measured at the 64K bf16 prefill:
+// 4 waves x 1 tile (two workgroups per CU) 9.6 ms; 8 waves x 1 or 2 tiles (one workgroup per CU,
+// the select no longer overlaps another query's scoring) 12.0 ms; deeper rings do not help because
+// the key tiles are L2 hits either way.
+constexpr int kNBuf = 1;
+constexpr int kFusedWaves = 4;
 
 enum : int { DT_F32 = 0, DT_BF16 = 1, DT_FP8 = 2 };
 
@@ -406,13 +408,17 @@ __global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
 }
 
 // Eq. 1 / Eq. 5 on MFMA for a causal prefill of ONE sequence with consecutive positions: one
-// workgroup of 8 waves = 8 consecutive queries; 64-key tiles are staged once in LDS (double
-// buffered) and shared by the 8 queries.  Used by the flat DSA indexer and by Stage 1.
+// workgroup of 8 waves = 8 consecutive queries; 64-key tiles (two 32-key sub-tiles) are DMA'd once
+// into LDS (double buffered, one barrier per tile) and shared by the 8 queries; each wave runs the
+// MFMAs of one sub-tile over the epilogue of the previous one (two accumulator sets).  Longest
+// prefixes launch first.  Used by the flat DSA indexer and by Stage 1.
 template <int HG, int KDT>
 __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
-  __shared__ uint4 tiles[2][2][kTileChunks];
-  const int g = gridDim.x - 1 - blockIdx.x;            // longest prefixes first
-  const int th = threadIdx.x, wave = th >> 6, lane = th & 63;
+  constexpr int BB = TileGeom<KDT>::kBufBytes;
+  __shared__ __align__(16) unsigned char tiles[2 * 2 * BB];   // [buffer][sub-tile]
+  const int g = gridDim.x - 1 - blockIdx.x;
+  const int th = threadIdx.x, lane = th & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(th >> 6);
   const int tl = g * 8 + wave;
   const bool active = tl < a.t_count;
   const int t = a.t_begin + (active ? tl : a.t_count - 1);
@@ -424,73 +430,80 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
   const int n_max = visible_rows(a, query_pos(a, a.t_begin + tl_last, seq_last));
   const int n_iter = (n_max + 63) >> 6;
   float* out = a.out + (long)(active ? tl : 0) * a.ld;
-  const char* kbase = (const char*)a.keys;
-  const float* sbase = a.k_scale;
 
   QFrag<HG> f;
   load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
 
-  // cooperative staging of a 64-key tile: bf16 1024 chunks (2 per thread), fp8 512 fetches (1)
-  constexpr int NF = KDT == DT_BF16 ? 2 : 1;
-  typedef uint32_t prevec __attribute__((ext_vector_type(4 * NF)));
-  prevec pre;
-  auto fetch = [&](int it) {
+  __amdgpu_buffer_rsrc_t krsrc, srsrc;
+  key_buffers<KDT>(a, 0, krsrc, srsrc);
+  const uint32_t tiles_addr = lds_address(tiles);
+  // this wave's share of the cooperative DMA of a 64-key tile: sub-tile wave / 4, an eighth of it
+  const int sub_w = wave >> 2, part_w = wave & 3;
+  int voff[2] = {0, 0};
+  if (KDT == DT_BF16) {
 #pragma unroll
-    for (int i = 0; i < NF; ++i) {
-      const int p = i * 512 + th;
-      long gr;
-      if (KDT == DT_BF16) {
-        const int sub = p >> 9, pp = p & 511, r = pp >> 4, c = pp & 15;
-        gr = (long)it * 64 + sub * 32 + r;
-        gr = gr < a.rows_per_seq ? gr : a.rows_per_seq - 1;
-        put4(pre, i, *reinterpret_cast<const uint4*>(kbase + (gr * kD + ((c ^ (r & 15)) << 3)) * 2));
-      } else {
-        const int sub = p >> 8, pp = p & 255, r = pp >> 3, c8 = pp & 7;
-        gr = (long)it * 64 + sub * 32 + r;
-        gr = gr < a.rows_per_seq ? gr : a.rows_per_seq - 1;
-        put4(pre, i, *reinterpret_cast<const uint4*>(kbase + gr * kD + (c8 << 4)));
-      }
+    for (int i = 0; i < 2; ++i) {
+      const int r = part_w * 8 + i * 4 + (lane >> 4), c = lane & 15;
+      voff[i] = (lane >> 4) * 256 + ((c ^ (r & 15)) << 4);
+    }
+  } else {
+    voff[0] = (lane >> 3) * 128 + (((lane & 7) ^ (lane >> 3)) << 4);
+  }
+  auto dma_tile = [&](int it, int buf) {
+    const uint32_t dst = tiles_addr + (buf * 2 + sub_w) * BB;
+    const int row0 = it * 64 + sub_w * 32 + part_w * 8;
+    if constexpr (KDT == DT_BF16) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, (lds_void*)(uintptr_t)(dst + (part_w * 128 + i * 64) * 16),
+                                                 16, voff[i], (row0 + i * 4) * 256, 0, 0);
+    } else {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, (lds_void*)(uintptr_t)(dst + part_w * 1024), 16, voff[0],
+                                               row0 * 128, 0, 0);
+      if (part_w == 0)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(srsrc, (lds_void*)(uintptr_t)(dst + 4096), 4, lane * 4,
+                                                 (it * 64 + sub_w * 32) * 4, 0, 0);
     }
   };
-  auto store = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < NF; ++i) {
-      const int p = i * 512 + th;
-      if (KDT == DT_BF16) {
-        tiles[buf][p >> 9][p & 511] = get4(pre, i);
-      } else {
-        const int sub = p >> 8, pp = p & 255, r = pp >> 3, c8 = pp & 7;
-        const uint2 x = fp8x4_to_bf16x4(pre[4 * i + 0]), y = fp8x4_to_bf16x4(pre[4 * i + 1]);
-        const uint2 z = fp8x4_to_bf16x4(pre[4 * i + 2]), u = fp8x4_to_bf16x4(pre[4 * i + 3]);
-        tiles[buf][sub][r * 16 + ((2 * c8) ^ (r & 15))] = make_uint4(x.x, x.y, y.x, y.y);
-        tiles[buf][sub][r * 16 + ((2 * c8 + 1) ^ (r & 15))] = make_uint4(z.x, z.y, u.x, u.y);
-      }
+  auto read_sub = [&](int buf, int sub, float& scale) -> u32x32 {
+    const uint32_t addr = tiles_addr + (buf * 2 + sub) * BB;
+    if constexpr (KDT == DT_BF16) {
+      scale = 1.f;
+      return lds_read_tile_raw(addr);
+    } else {
+      scale = lds_read_f32_raw(addr + 4096 + (lane & 31) * 4);
+      return lds_read_tile_fp8_raw(addr);
     }
+  };
+  // sub-tile u covers rows 32u .. 32u+31
+  auto finish = [&](int u, float s) {
+    const int row = u * 32 + (lane & 31);
+    if (lane < 32 && row < n_vis) out[row] = s;
   };
 
-  if (n_iter > 0) {
-    fetch(0);
-    store(0);
-  }
+  if (n_iter > 0) dma_tile(0, 0);
   qfrag_ready<HG>(f);
+  wait_vmem_le<0>();
   __syncthreads();
-  int cur = 0;
+  accvec<HG> acc_a, acc_b;
+  float sc_a = 1.f, sc_b = 1.f;
   for (int it = 0; it < n_iter; ++it) {
-    if (it + 1 < n_iter) fetch(it + 1);
-#pragma unroll
-    for (int sub = 0; sub < 2; ++sub) {
-      const int s0 = it * 64 + sub * 32;
-      if (s0 < n_vis) {
-        float s = score_tile<HG>(f, tiles[cur][sub]);
-        const int row = s0 + (lane & 31);
-        if (KDT == DT_FP8) s *= sbase[row < a.rows_per_seq ? row : (int)a.rows_per_seq - 1];
-        if (lane < 32 && row < n_vis) out[row] = s;
-      }
+    const int buf = it & 1;
+    if (it + 1 < n_iter) dma_tile(it + 1, buf ^ 1);
+    {
+      const u32x32 kv = read_sub(buf, 0, sc_b);
+      acc_b = mfma_tile<HG>(f, kv);                                        // sub-tile 2it
+      if (it > 0) finish(2 * it - 1, tile_epilogue<HG>(f, acc_a) * sc_a);  // previous tile's second half
     }
-    if (it + 1 < n_iter) store(cur ^ 1);
+    {
+      const u32x32 kv = read_sub(buf, 1, sc_a);
+      acc_a = mfma_tile<HG>(f, kv);                                        // sub-tile 2it+1
+      finish(2 * it, tile_epilogue<HG>(f, acc_b) * sc_b);
+    }
+    wait_vmem_le<0>();   // the next tile (and this wave's score stores) have landed
     __syncthreads();
-    cur ^= 1;
   }
+  if (n_iter > 0) finish(2 * n_iter - 1, tile_epilogue<HG>(f, acc_a) * sc_a);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -578,21 +591,20 @@ __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Stage 2 fused (Eqs. 7-9): one workgroup of 4 waves per query scores every tile of the kept
-// blocks into LDS and selects the top k there; only the k indices leave the CU.
-template <int HG, int KDT, int E>
-__global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int32_t* topk_idx,
-                                                         float* topk_scores) {
+// Stage 2 fused (Eqs. 7-9): one workgroup of NW waves per query scores every tile of the kept
+// blocks into LDS and selects the top k there; only the k indices leave the CU.  E = candidates
+// per thread in the select (NW * 64 * E >= m * B).  LDS: the per-wave tile rings, then the m*B
+// scores; the select's scratch reuses the ring once scoring is over.
+template <int HG, int KDT, int NW, int NB, int E>
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(ScoreArgs a, int k,
+                                                                           int32_t* topk_idx,
+                                                                           float* topk_scores) {
   extern __shared__ __align__(16) unsigned char smem[];
-  constexpr int NB = kNBuf;
-  constexpr size_t kStageBytes = (size_t)4 * NB * TileGeom<KDT>::kBufBytes;
+  constexpr int NT = NW * 64;
+  constexpr size_t kStageBytes = (size_t)NW * NB * TileGeom<KDT>::kBufBytes;
+  static_assert(sizeof(SelectSmem<NT, E>) <= kStageBytes, "select scratch must fit the rings");
   float* sc = reinterpret_cast<float*>(smem + kStageBytes);   // m*B scores (swizzled: score_slot)
-  const int n_slots = a.m * a.B;
-  SelectSmem<256, E>& sm =
-      *reinterpret_cast<SelectSmem<256, E>*>(smem + kStageBytes + (size_t)n_slots * 4);
-  int32_t* blk_ids = reinterpret_cast<int32_t*>(smem + kStageBytes + (size_t)n_slots * 4 +
-                                                sizeof(SelectSmem<256, E>));
-  int32_t* n_used_p = blk_ids + a.m;
+  SelectSmem<NT, E>& sm = *reinterpret_cast<SelectSmem<NT, E>*>(smem);
   const int t = a.t_begin + (gridDim.x - 1 - blockIdx.x);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   int seq;
@@ -602,20 +614,22 @@ __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int
   QFrag<HG> f;
   load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
 
-  // kept block ids of this query; tile v = sub-tile v % tpb of slot v / tpb.  Only the slots up to
-  // the last kept block are walked (a short prefix keeps few blocks).
+  // Only the slots up to the last kept block are walked (a short prefix keeps few blocks).
+  // Tile v = sub-tile v % tpb of slot v / tpb; wave w takes tiles w, w + NW, ...
   const int tpb = a.B >> 5;
   const int n_blocks = (int)(a.rows_per_seq / a.B);
-  if (threadIdx.x == 0) *n_used_p = 0;
-  __syncthreads();
-  for (int i = threadIdx.x; i < a.m; i += 256) {
-    const int blk = a.block_idx[(long)t * a.m + i];
-    blk_ids[i] = blk;
-    if (blk >= 0 && blk < n_blocks) atomicMax(n_used_p, i + 1);
+  const int32_t* blk_ids = a.block_idx + (long)t * a.m;
+  int n_used = 0;
+  for (int i = lane; i < a.m; i += 64) {
+    const int blk = blk_ids[i];
+    if (blk >= 0 && blk < n_blocks) n_used = i + 1;
   }
-  __syncthreads();
-  const int n_active = __builtin_amdgcn_readfirstlane(*n_used_p) * tpb;
-  qfrag_ready<HG>(f);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const int o = __shfl_xor(n_used, off);
+    n_used = o > n_used ? o : n_used;
+  }
+  const int n_active = __builtin_amdgcn_readfirstlane(n_used) * tpb;
   // first key row of tile v, or -1 if its slot is empty / out of range / not visible
   auto row_of = [&](int v) -> int {
     const int slot = v / tpb;
@@ -623,27 +637,27 @@ __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int
     const int row0 = blk * a.B + (v - slot * tpb) * 32;
     return (blk < 0 || blk >= n_blocks || row0 >= n_vis) ? -1 : row0;
   };
-  const int nj = n_active > wave ? (n_active - wave + 3) >> 2 : 0;   // tiles of this wave
-  // lane j holds the first key row of this wave's j-th tile (wave + 4j)
+  const int nj = n_active > wave ? (n_active - wave + NW - 1) / NW : 0;   // tiles of this wave
+  // lane j holds the first key row of this wave's j-th tile (wave + NW * j)
   LaneTable rows;
-  rows.lo = row_of(wave + 4 * (lane < nj ? lane : 0));
-  rows.hi = (nj > 64) ? row_of(wave + 4 * (lane + 64 < nj ? lane + 64 : 0)) : -1;
+  rows.lo = row_of(wave + NW * (lane < nj ? lane : 0));
+  rows.hi = (nj > 64) ? row_of(wave + NW * (lane + 64 < nj ? lane + 64 : 0)) : -1;
+  qfrag_ready<HG>(f);
   __amdgpu_buffer_rsrc_t krsrc, srsrc;
   key_buffers<KDT>(a, seq, krsrc, srsrc);
+  auto row_at = [&](int j) {
+    const int r = rows.at(j);
+    return r < 0 ? 0 : r;   // a tile without visible keys still flows through, masked below
+  };
+  auto finish = [&](int j, float s) {
+    const int r = rows.at(j);
+    const int row = (r < 0 ? 0 : r) + (lane & 31);
+    if (row >= (r < 0 ? 0 : n_vis)) s = neg_inf();
+    if (lane < 32) sc[score_slot((wave + NW * j) * 32 + lane)] = s;
+  };
   const uint32_t ring_addr = lds_address(smem) + wave * NB * TileGeom<KDT>::kBufBytes;
-  wave_pipeline<HG, KDT, NB>(
-      f, krsrc, srsrc, ring_addr, nj,
-      [&](int j) {
-        const int r = rows.at(j);
-        return r < 0 ? 0 : r;   // a tile without visible keys still flows through, masked below
-      },
-      [&](int j, float s) {
-        const int r = rows.at(j);
-        const int row = (r < 0 ? 0 : r) + (lane & 31);
-        if (row >= (r < 0 ? 0 : n_vis)) s = neg_inf();
-        if (lane < 32) sc[score_slot((wave + 4 * j) * 32 + lane)] = s;
-      });
-  __syncthreads();
+  wave_pipeline<HG, KDT, NB>(f, krsrc, srsrc, ring_addr, nj, row_at, finish);
+  __syncthreads();   // scores complete, rings dead: the select scratch may overwrite them
   const int n_cand_slots = n_active * 32;   // score slots actually written
 
   int32_t* oi = topk_idx + (long)t * k;
@@ -658,8 +672,8 @@ __global__ __launch_bounds__(256, 2) void k_refine_fused(ScoreArgs a, int k, int
     oi[p] = blk_ids[slot] * a.B + (i - slot * a.B);
     if (os) os[p] = key_to_score(key);
   };
-  const int n_out = select_topk<256, E>(sm, n_cand_slots, k, load4, load1, emit);
-  for (int p = n_out + threadIdx.x; p < k; p += 256) {
+  const int n_out = select_topk<NT, E>(sm, n_cand_slots, k, load4, load1, emit);
+  for (int p = n_out + threadIdx.x; p < k; p += NT) {
     oi[p] = -1;
     if (os) os[p] = neg_inf();
   }
