@@ -137,6 +137,38 @@ int dsa_flat_indexer_topk(const hisa_queries* queries, const hisa_keys* keys, in
                           int32_t* topk_idx, float* topk_scores, void* ws, size_t ws_bytes,
                           void* stream);
 
+/*
+ * Incremental maintenance of the pooled-key cache (Section 4.1: the pooled keys "can be
+ * incrementally maintained alongside the KV cache"; Section 4.2 assumes it).  After sequence n grew
+ * from prev_len[n] to keys->seq_len[n] tokens (appended at the end), recomputes exactly the pooled
+ * keys of the blocks that received tokens: blocks prev_len[n] / B .. (seq_len[n] - 1) / B.  The
+ * result is bit-identical to hisa_pool_blocks over the whole sequence.
+ *   prev_len       [n_seq] int32 (device): lengths at the previous update (0 for a new sequence)
+ *   max_new_tokens host bound on seq_len[n] - prev_len[n] over all sequences (sizes the launch);
+ *                  growth beyond it is NOT pooled
+ *   pooled         [n_seq, s_max / B, d] (device, in/out)
+ */
+int hisa_pool_append(const hisa_keys* keys, int32_t B, const int32_t* prev_len, int32_t max_new_tokens,
+                     void* pooled, int32_t pooled_dtype, void* stream);
+
+/*
+ * Block-Sparse baseline of the paper's evaluation (Section 5: Stage 1 only, every token of the kept
+ * blocks is attended): expands block_idx into token positions.
+ *   tokens [T, m * B] int32 (device, out): slot c = block_idx[t, c / B] * B + c % B if that token
+ *   is visible to the query (<= q_pos), else -1.  With block_idx as Stage 1 writes it (ascending,
+ *   own block last) the valid entries are ascending and the -1 entries form the tail.
+ */
+int hisa_block_sparse_tokens(const hisa_queries* queries, const hisa_keys* keys, int32_t B, int32_t m,
+                             const int32_t* block_idx, int32_t* tokens, void* stream);
+
+/*
+ * Selection-consistency diagnostic (Eq. 12): iou[t] = |A_t & B_t| / |A_t | B_t| for two index
+ * tensors [T, k] whose rows are ascending with -1 padding at the end (as this library writes
+ * them); two empty rows give 1.  iou: [T] fp32 (device, out).
+ */
+int hisa_index_iou(const int32_t* a_idx, const int32_t* b_idx, int32_t T, int32_t k, float* iou,
+                   void* stream);
+
 /* Recommended workspace size in bytes for `op` (HISA_OP_*) at these shapes; 0 if none is needed
  * or the shapes are invalid.  `want_scores` != 0: the optional full score output of Stage 1 / 2
  * is requested (which then replaces the workspace). */

@@ -246,6 +246,66 @@ int hisa_pool_blocks(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_
   return launch_status();
 }
 
+int hisa_pool_append(const hisa_keys* keys, int32_t B, const int32_t* prev_len, int32_t max_new_tokens,
+                     void* pooled, int32_t pooled_dtype, void* stream) {
+  int st = check_keys(keys, true);
+  if (st) return st;
+  if (!pooled || !prev_len) return HISA_ERR_NULL;
+  if (B < 1 || keys->s_max % B || max_new_tokens < 0) return HISA_ERR_SHAPE;
+  const int kd = keys->k_dtype, d = keys->d;
+  const int vec = kd == HISA_F32 ? 4 : (kd == HISA_BF16 ? 8 : 16);
+  if (d % vec || d / vec > 256) return HISA_ERR_SHAPE;
+  if (!((kd == HISA_F32 && pooled_dtype == HISA_F32) ||
+        (kd != HISA_F32 && (pooled_dtype == HISA_BF16 || pooled_dtype == HISA_F32))))
+    return HISA_ERR_DTYPE;
+  if (max_new_tokens == 0) return HISA_OK;
+  // max_new_tokens appended tokens touch at most this many blocks (the first may be partial)
+  const int n_blk = (max_new_tokens + B - 2) / B + 1;
+  hipStream_t s = (hipStream_t)stream;
+  dim3 grid(n_blk, keys->n_seq);
+#define POOLA(KD, PD)                                                                            \
+  hipLaunchKernelGGL((k_pool_append<KD, PD>), grid, dim3(256), 0, s, keys->k, keys->k_scale,     \
+                     keys->seq_len, prev_len, (long)keys->s_max, d, B, pooled)
+  if (kd == HISA_F32) POOLA(DT_F32, DT_F32);
+  else if (kd == HISA_BF16 && pooled_dtype == HISA_BF16) POOLA(DT_BF16, DT_BF16);
+  else if (kd == HISA_BF16) POOLA(DT_BF16, DT_F32);
+  else if (pooled_dtype == HISA_BF16) POOLA(DT_FP8, DT_BF16);
+  else POOLA(DT_FP8, DT_F32);
+#undef POOLA
+  return launch_status();
+}
+
+int hisa_block_sparse_tokens(const hisa_queries* queries, const hisa_keys* keys, int32_t B, int32_t m,
+                             const int32_t* block_idx, int32_t* tokens, void* stream) {
+  if (!queries || !keys || !keys->seq_len) return HISA_ERR_NULL;
+  if (!block_idx || !tokens) return HISA_ERR_NULL;
+  if (queries->T < 1 || keys->n_seq < 1 || keys->s_max < 1) return HISA_ERR_SHAPE;
+  if (B < 1 || keys->s_max % B || m < 1 || m > kMaxM || (long)m * B > kMaxCand) return HISA_ERR_SHAPE;
+  ScoreArgs a{};
+  a.q_seq = queries->q_seq;
+  a.q_pos = queries->q_pos;
+  a.q_pos0 = queries->q_pos0;
+  a.seq_len = keys->seq_len;
+  a.n_seq = keys->n_seq;
+  a.rows_per_seq = keys->s_max;
+  a.block_idx = block_idx;
+  a.m = m;
+  a.B = B;
+  const int gx = (m * B + 255) / 256;
+  hipLaunchKernelGGL(k_block_sparse_tokens, dim3(gx > 16 ? 16 : gx, queries->T), dim3(256), 0,
+                     (hipStream_t)stream, a, tokens);
+  return launch_status();
+}
+
+int hisa_index_iou(const int32_t* a_idx, const int32_t* b_idx, int32_t T, int32_t k, float* iou,
+                   void* stream) {
+  if (!a_idx || !b_idx || !iou) return HISA_ERR_NULL;
+  if (T < 1 || k < 1) return HISA_ERR_SHAPE;
+  hipLaunchKernelGGL(k_index_iou, dim3((T + 255) / 256), dim3(256), 0, (hipStream_t)stream, a_idx, b_idx,
+                     T, k, iou);
+  return launch_status();
+}
+
 int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, const void* pooled,
                           int32_t pooled_dtype, int32_t B, int32_t m, int32_t* block_idx,
                           float* block_scores, void* ws, size_t ws_bytes, void* stream) {

@@ -59,20 +59,16 @@ __device__ __forceinline__ int visible_rows(const ScoreArgs& a, int pos) {
 // load (4 fp32 / 8 bf16 / 16 fp8).  Thread (rl, col) sums rows rl, rl+RP, ... of its 16-byte
 // column in fp32; the RP partial rows are then reduced through LDS and divided by the count.
 template <int KDT, int PDT>
-__global__ __launch_bounds__(256) void k_pool(const void* __restrict__ keys,
-                                              const float* __restrict__ k_scale,
-                                              const int32_t* __restrict__ seq_len, long s_max, int d,
-                                              int B, int blk_begin, void* __restrict__ pooled) {
+__device__ __forceinline__ void pool_one_block(const void* __restrict__ keys,
+                                               const float* __restrict__ k_scale, int sl, long s_max,
+                                               int d, int B, int seq, int b, void* __restrict__ pooled,
+                                               float* part) {
   constexpr int VEC = KDT == DT_F32 ? 4 : (KDT == DT_BF16 ? 8 : 16);
-  __shared__ float part[256 * VEC];
-  const int seq = blockIdx.y;
-  const int b = blk_begin + blockIdx.x;
   const int tid = threadIdx.x;
   const int VC = d / VEC;               // 16-byte columns per key row (<= 256 checked on the host)
   const int RP = 256 / VC;              // rows in flight per pass
   const int rl = tid / VC, col = tid % VC;
   const long M = s_max / B;
-  const int sl = seq_len[seq];
   long lo = (long)b * B;
   int nb = (int)((sl - lo) < (long)B ? (sl - lo) : (long)B);
   if (nb < 0) nb = 0;
@@ -122,6 +118,77 @@ __global__ __launch_bounds__(256) void k_pool(const void* __restrict__ keys,
     else
       ((uint16_t*)pooled)[o] = f32_to_bf16_rne(mean);
   }
+}
+
+template <int KDT, int PDT>
+__global__ __launch_bounds__(256) void k_pool(const void* __restrict__ keys,
+                                              const float* __restrict__ k_scale,
+                                              const int32_t* __restrict__ seq_len, long s_max, int d,
+                                              int B, int blk_begin, void* __restrict__ pooled) {
+  constexpr int VEC = KDT == DT_F32 ? 4 : (KDT == DT_BF16 ? 8 : 16);
+  __shared__ float part[256 * VEC];
+  const int seq = blockIdx.y;
+  pool_one_block<KDT, PDT>(keys, k_scale, seq_len[seq], s_max, d, B, seq, blk_begin + blockIdx.x,
+                           pooled, part);
+}
+
+// Incremental pooled-cache update (Section 4.1): workgroup (j, n) re-pools block prev_len[n]/B + j
+// of sequence n if that block received tokens since the previous update.
+template <int KDT, int PDT>
+__global__ __launch_bounds__(256) void k_pool_append(const void* __restrict__ keys,
+                                                     const float* __restrict__ k_scale,
+                                                     const int32_t* __restrict__ seq_len,
+                                                     const int32_t* __restrict__ prev_len, long s_max,
+                                                     int d, int B, void* __restrict__ pooled) {
+  constexpr int VEC = KDT == DT_F32 ? 4 : (KDT == DT_BF16 ? 8 : 16);
+  __shared__ float part[256 * VEC];
+  const int seq = blockIdx.y;
+  int sl = seq_len[seq];
+  sl = sl < 0 ? 0 : (sl > s_max ? (int)s_max : sl);
+  int pl = prev_len[seq];
+  pl = pl < 0 ? 0 : (pl > sl ? sl : pl);
+  if (sl <= pl) return;                       // nothing appended (uniform per workgroup)
+  const int b = pl / B + blockIdx.x;
+  if (b > (sl - 1) / B) return;
+  pool_one_block<KDT, PDT>(keys, k_scale, sl, s_max, d, B, seq, b, pooled, part);
+}
+
+// Block-Sparse baseline (Section 5): every visible token of the kept blocks.
+__global__ __launch_bounds__(256) void k_block_sparse_tokens(ScoreArgs a, int32_t* __restrict__ tokens) {
+  const int t = blockIdx.y;
+  int seq;
+  const int pos = query_pos(a, t, seq);
+  const int n_slots = a.m * a.B;
+  const int n_blocks = (int)(a.rows_per_seq / a.B);
+  for (int c = blockIdx.x * 256 + threadIdx.x; c < n_slots; c += gridDim.x * 256) {
+    const int slot = c / a.B;
+    const int blk = a.block_idx[(long)t * a.m + slot];
+    const int tok = blk * a.B + (c - slot * a.B);
+    tokens[(long)t * n_slots + c] = (blk >= 0 && blk < n_blocks && tok <= pos) ? tok : -1;
+  }
+}
+
+// Eq. 12: one thread per row merges two ascending index rows.
+__global__ __launch_bounds__(256) void k_index_iou(const int32_t* __restrict__ a_idx,
+                                                   const int32_t* __restrict__ b_idx, int T, int k,
+                                                   float* __restrict__ iou) {
+  const int t = blockIdx.x * 256 + threadIdx.x;
+  if (t >= T) return;
+  const int32_t* pa = a_idx + (long)t * k;
+  const int32_t* pb = b_idx + (long)t * k;
+  int i = 0, j = 0, inter = 0;
+  while (i < k && j < k) {
+    const int x = pa[i], y = pb[j];
+    if (x < 0 || y < 0) break;
+    if (x == y) { ++inter; ++i; ++j; }
+    else if (x < y) ++i;
+    else ++j;
+  }
+  int na = i, nbv = j;
+  while (na < k && pa[na] >= 0) ++na;
+  while (nbv < k && pb[nbv] >= 0) ++nbv;
+  const int uni = na + nbv - inter;
+  iou[t] = uni == 0 ? 1.f : (float)inter / (float)uni;
 }
 
 // ------------------------------------------------------------------------------------------

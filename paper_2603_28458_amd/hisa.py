@@ -18,8 +18,9 @@ OP_POOL, OP_BLOCK_SCORE_TOPK, OP_TOKEN_REFINE_TOPK, OP_FLAT_TOPK = 0, 1, 2, 3
 DTYPE_CODE = {"f32": HISA_F32, "bf16": HISA_BF16, "fp8_e4m3": HISA_FP8_E4M3}
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libhisa.so")
 
-EXPORTS = ["hisa_pool_blocks", "hisa_block_score_topk", "hisa_token_refine_topk",
-           "dsa_flat_indexer_topk", "hisa_workspace_bytes", "hisa_status_string", "hisa_version"]
+EXPORTS = ["hisa_pool_blocks", "hisa_pool_append", "hisa_block_score_topk", "hisa_token_refine_topk",
+           "hisa_block_sparse_tokens", "hisa_index_iou", "dsa_flat_indexer_topk", "hisa_workspace_bytes",
+           "hisa_status_string", "hisa_version"]
 
 
 class HisaError(RuntimeError):
@@ -52,6 +53,12 @@ def lib() -> C.CDLL:
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         L.hisa_pool_blocks.argtypes = [C.POINTER(_Keys), i32, i32, i32, vp, i32, vp]
         L.hisa_pool_blocks.restype = C.c_int
+        L.hisa_pool_append.argtypes = [C.POINTER(_Keys), i32, vp, i32, vp, i32, vp]
+        L.hisa_pool_append.restype = C.c_int
+        L.hisa_block_sparse_tokens.argtypes = [C.POINTER(_Queries), C.POINTER(_Keys), i32, i32, vp, vp, vp]
+        L.hisa_block_sparse_tokens.restype = C.c_int
+        L.hisa_index_iou.argtypes = [vp, vp, i32, i32, vp, vp]
+        L.hisa_index_iou.restype = C.c_int
         L.hisa_block_score_topk.argtypes = [C.POINTER(_Queries), C.POINTER(_Keys), vp, i32, i32, i32,
                                             vp, vp, vp, sz, vp]
         L.hisa_block_score_topk.restype = C.c_int
@@ -171,6 +178,40 @@ def hisa_pool_blocks(keys: Keys, B: int, pooled: Optional[torch.Tensor] = None,
                                 _ptr(pooled), pooled_dtype, _stream(stream))
     _check(st, "hisa_pool_blocks")
     return pooled
+
+
+def hisa_pool_append(keys: Keys, B: int, prev_len: torch.Tensor, max_new_tokens: int, pooled: torch.Tensor,
+                     pooled_dtype: int = HISA_BF16, stream=None) -> torch.Tensor:
+    """Section 4.1, incremental pooled cache: re-pools the blocks that grew since prev_len."""
+    kc = keys.c()
+    st = lib().hisa_pool_append(C.byref(kc), B, _ptr(prev_len), max_new_tokens, _ptr(pooled), pooled_dtype,
+                                _stream(stream))
+    _check(st, "hisa_pool_append")
+    return pooled
+
+
+def hisa_block_sparse_tokens(queries: Queries, keys: Keys, B: int, m: int, block_idx: torch.Tensor,
+                             tokens: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Block-Sparse baseline (Section 5): tokens [T, m*B] int32, -1 where not visible."""
+    if tokens is None:
+        tokens = torch.empty((queries.T, m * B), dtype=torch.int32, device=block_idx.device)
+    qc, kc = queries.c(), keys.c()
+    st = lib().hisa_block_sparse_tokens(C.byref(qc), C.byref(kc), B, m, _ptr(block_idx), _ptr(tokens),
+                                        _stream(stream))
+    _check(st, "hisa_block_sparse_tokens")
+    return tokens
+
+
+def hisa_index_iou(a_idx: torch.Tensor, b_idx: torch.Tensor, iou: Optional[torch.Tensor] = None,
+                   stream=None) -> torch.Tensor:
+    """Eq. 12 per row of two [T, k] index tensors (ascending rows, -1 padding)."""
+    T, k = a_idx.shape
+    assert b_idx.shape == a_idx.shape
+    if iou is None:
+        iou = torch.empty((T,), dtype=torch.float32, device=a_idx.device)
+    st = lib().hisa_index_iou(_ptr(a_idx), _ptr(b_idx), T, k, _ptr(iou), _stream(stream))
+    _check(st, "hisa_index_iou")
+    return iou
 
 
 def hisa_block_score_topk(queries: Queries, keys: Keys, pooled: torch.Tensor, pooled_dtype: int, B: int,

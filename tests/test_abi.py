@@ -75,6 +75,20 @@ def test_host_side_validation_rejects_before_launch(lib):
     assert lib.dsa_flat_indexer_topk(C.byref(q3), C.byref(k), 64, fake, None, fake, 1 << 30, None) == 6
 
 
+def test_validation_of_the_auxiliary_entry_points(lib):
+    fake = 0x1000
+    q, k = _structs()
+    assert lib.hisa_pool_append(C.byref(k), 128, None, 16, fake, 1, None) == 1
+    assert lib.hisa_pool_append(C.byref(k), 100, fake, 16, fake, 1, None) == 2
+    assert lib.hisa_pool_append(C.byref(k), 128, fake, -1, fake, 1, None) == 2
+    assert lib.hisa_pool_append(C.byref(k), 128, fake, 16, fake, 2, None) == 3
+    assert lib.hisa_pool_append(C.byref(k), 128, fake, 0, fake, 1, None) == 0      # nothing to do, no launch
+    assert lib.hisa_block_sparse_tokens(C.byref(q), C.byref(k), 128, 8, None, fake, None) == 1
+    assert lib.hisa_block_sparse_tokens(C.byref(q), C.byref(k), 96, 8, fake, fake, None) == 2
+    assert lib.hisa_index_iou(None, fake, 4, 4, fake, None) == 1
+    assert lib.hisa_index_iou(fake, fake, 0, 4, fake, None) == 2
+
+
 def test_workspace_sizes(lib):
     q, k = _structs(T=65536, s_max=65536)
     assert lib.hisa_workspace_bytes(hisa.OP_POOL, C.byref(q), C.byref(k), 128, 64, 2048, 0) == 0

@@ -117,3 +117,64 @@ def test_run_to_run_determinism():
         outs.append((pooled.clone(), bi.clone(), ti.clone(), fi.clone()))
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+
+
+def test_incremental_pooled_cache_matches_full_pool_and_oracle():
+    # Section 4.1: the pooled cache is maintained while sequences grow (decode).  Grow three sequences
+    # by different amounts (within a block, across one boundary, across several) and compare the
+    # incrementally updated cache with a full re-pool (bit-exact) and with the oracle's block means.
+    from oracle import hisa_oracle as O
+    from paper_2603_28458_amd import hisa
+    from tests.parity import _np
+    from tests.util import check_scores
+    for k_dtype in ("bf16", "fp8_e4m3"):
+        wl = W.make_workload(f"append_{k_dtype}", n_seq=4, seq_len=[700, 1024, 333, 64], T=4, H=64, d=128, B=128,
+                             m=4, k=128, q_dtype="bf16", k_dtype=k_dtype, mode="decode", seed=120)
+        print(f"\n[parity] {wl.name}", flush=True)
+        Q, K = hisa.to_device(wl)
+        prev = np.array([650, 600, 0, 64], dtype=np.int32)          # last one: nothing appended
+        K_prev = hisa.Keys(k=K.k, seq_len=torch.from_numpy(prev).cuda(), dtype=K.dtype, k_scale=K.k_scale)
+        pooled = hisa.hisa_pool_blocks(K_prev, wl.B)                 # cache as of the previous lengths
+        hisa.hisa_pool_append(K, wl.B, K_prev.seq_len, 450, pooled)  # bound >= every growth
+        full = hisa.hisa_pool_blocks(K, wl.B)
+        torch.cuda.synchronize()
+        M = wl.s_max // wl.B
+        for n in range(4):                                           # blocks that hold tokens now
+            nb = -(-int(wl.seq_len[n]) // wl.B)
+            assert torch.equal(pooled[n, :nb], full[n, :nb]), n
+        want = O.pool_blocks(wl.keys, wl.k_dtype, wl.k_scale, wl.seq_len, wl.B, "bf16")
+        check_scores(O.decode(_np(full), "bf16").reshape(-1, wl.d), O.decode(want, "bf16").reshape(-1, wl.d), 2e-2,
+                     "pooled keys")
+        # a growth beyond the stated bound is (by contract) not pooled: only the first blocks change
+        pooled2 = hisa.hisa_pool_blocks(K_prev, wl.B)
+        hisa.hisa_pool_append(K, wl.B, K_prev.seq_len, 0, pooled2)
+        torch.cuda.synchronize()
+        assert torch.equal(pooled2, hisa.hisa_pool_blocks(K_prev, wl.B))
+
+
+def test_block_sparse_tokens_and_iou_diagnostic():
+    # Block-Sparse baseline (Section 5) = all visible tokens of the kept blocks (Eq. 7 + causal mask),
+    # and the IoU of Eq. 12 between HISA's and the flat indexer's selections.
+    from oracle import hisa_oracle as O
+    from paper_2603_28458_amd import hisa
+    wl = W.make_workload("bsparse", seq_len=2500, T=2500, H=64, d=128, B=128, m=5, k=256, q_dtype="bf16",
+                         k_dtype="bf16", seed=121)
+    print(f"\n[parity] {wl.name}", flush=True)
+    Q, K = hisa.to_device(wl)
+    pooled = hisa.hisa_pool_blocks(K, wl.B)
+    bi, _ = hisa.hisa_block_score_topk(Q, K, pooled, hisa.HISA_BF16, wl.B, wl.m)
+    toks = hisa.hisa_block_sparse_tokens(Q, K, wl.B, wl.m, bi)
+    ti, _, _ = hisa.hisa_token_refine_topk(Q, K, wl.B, wl.m, bi, wl.k)
+    fi, _ = hisa.dsa_flat_indexer_topk(Q, K, wl.k)
+    iou = hisa.hisa_index_iou(ti, fi)
+    torch.cuda.synchronize()
+    bi_h, toks_h, ti_h, fi_h, iou_h = (x.cpu().numpy() for x in (bi, toks, ti, fi, iou))
+    pos = wl.positions()
+    for t in range(0, wl.T, 7):
+        C = bi_h[t][bi_h[t] >= 0].astype(np.int64)
+        want = O.candidate_tokens(C, int(pos[t]), wl.B)
+        row = toks_h[t]
+        assert np.array_equal(row[:want.size], want), t
+        assert np.all(row[want.size:] == -1), t
+        assert abs(iou_h[t] - O.iou(ti_h[t], fi_h[t])) < 1e-6, t
+    assert torch.all(hisa.hisa_index_iou(ti, ti) == 1.0)

@@ -40,7 +40,7 @@ def check_scores(got, want, rtol, what=""):
     assert np.array_equal(np.isneginf(got), np.isneginf(want)), f"{what}: -inf mask differs"
     A = np.where(fin, np.abs(want), 0.0).max(axis=-1, keepdims=True)
     bound = rtol * np.maximum(np.abs(np.where(fin, want, 0.0)), A)
-    err = np.abs(np.where(fin, got - want, 0.0))
+    err = np.abs(np.where(fin, got, 0.0) - np.where(fin, want, 0.0))
     bad = err > bound
     assert not bad.any(), (f"{what}: {bad.sum()} scores out of tolerance; worst "
                            f"{(err / np.maximum(bound, 1e-300)).max():.3g} x bound")
