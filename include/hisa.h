@@ -105,7 +105,7 @@ int hisa_pool_blocks(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_
  *   pooled       [n_seq, s_max / B, d] of pooled_dtype (device, in)
  *   block_idx    [T, m] int32 (device, out): kept block ids ascending, then -1
  *   block_scores [T, s_max / B] fp32 (device, out) or NULL: J_{t,b} for b <= b_t, -inf beyond
- * Workspace: T * round_up(s_max / B, 64) floats when block_scores is NULL, else none.
+ * Workspace: T * (s_max / B) floats when block_scores is NULL, else none.
  */
 int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, const void* pooled,
                           int32_t pooled_dtype, int32_t B, int32_t m, int32_t* block_idx,

@@ -11,8 +11,15 @@ namespace hisa {
 
 // Fused Stage 2 kernel: waves per query and LDS tiles per wave.  Measured at the 64K bf16 prefill:
 // 4 waves x 1 tile (two workgroups per CU) 9.6 ms; 8 waves x 1 or 2 tiles (one workgroup per CU,
-// the select no longer overlaps another query's scoring) 12.0 ms; deeper rings do not help because
-// the key tiles are L2 hits either way.
+// the select no longer overlaps another query's scoring) 12.0 ms; 6 waves under a 168-register cap
+// (three waves per SIMD, one accumulator live, no overlap inside a wave, no spills) 13.6 ms: the
+// MFMA-over-epilogue overlap inside a wave is worth more than a third wave.  Deeper rings do not
+// help, neither do LDS reads requested half a tile early, a branch-free step with one DMA
+// instruction per MFMA pair, a raised wave priority over the MFMAs, or touching the lines of the
+// tiles two ahead (all within 2 % or slower): with bf16 keys a tile is 8 KB through the CU's
+// vector-memory path per 16 MFMAs, and that path (about 44 B/clk/CU measured, keys L2-resident)
+// saturates together with the matrix cores; with fp8 keys the widening puts the step just past
+// the rate at which vector instructions still issue under the MFMAs.
 constexpr int kNBuf = 1;
 constexpr int kFusedWaves = 4;
 
@@ -734,9 +741,18 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
     return make_uint4(ordered_key(v.x), ordered_key(v.y), ordered_key(v.z), ordered_key(v.w));
   };
   auto load1 = [&](int i) -> uint32_t { return ordered_key(sc[score_slot(i)]); };
+  // A thread's E consecutive candidates lie in one kept block when E divides B: its token base is
+  // then fetched once, not per emitted candidate.
+  const bool one_slot = a.B % E == 0;
+  const int my_slot = (int)(threadIdx.x * E) / a.B;
+  const int my_base = (one_slot && my_slot < a.m) ? (blk_ids[my_slot] - my_slot) * a.B : 0;
   auto emit = [&](int p, int i, uint32_t key) {
-    const int slot = i / a.B;
-    oi[p] = blk_ids[slot] * a.B + (i - slot * a.B);
+    if (one_slot) {
+      oi[p] = my_base + i;
+    } else {
+      const int slot = i / a.B;
+      oi[p] = blk_ids[slot] * a.B + (i - slot * a.B);
+    }
     if (os) os[p] = key_to_score(key);
   };
   const int n_out = select_topk<NT, E>(sm, n_cand_slots, k, load4, load1, emit);
