@@ -105,15 +105,90 @@ def cpu_baseline(wl, budget_s=20.0, seed=0):
                       f"float64 numpy ({spent:.1f} s); pooling all keys once took {t_pool:.2f} s extra"}
 
 
+def needle_recall(wl, block_idx, topk_idx, flat_idx):
+    """Synthetic-data diagnostic: a needle key is a scaled copy of one head of its target query, so
+    the target query should keep the needle's block (Stage 1) and select the needle token."""
+    pos = wl.positions()
+    n = blk = tok = flat = 0
+    for (_, p, t_star, _) in wl.needles:
+        if p > pos[t_star]:
+            continue
+        n += 1
+        blk += int((block_idx[t_star] == p // wl.B).any().item())
+        tok += int((topk_idx[t_star] == p).any().item())
+        flat += int((flat_idx[t_star] == p).any().item())
+    return {"n": n, "block_kept_by_stage1": blk, "token_selected_by_hisa": tok, "token_selected_by_flat": flat}
+
+
+def sweep(a, torch, hisa, W):
+    """Kernel-latency shapes of the paper (Sec. 5.1, Fig. 2) and its (B, m) ablation shapes (App. C)."""
+    shapes = []
+    if a.sweep == "context":
+        for L in (8192, 16384, 32768, 65536):
+            shapes.append((L, 128, 64, "budget 8192"))
+            shapes.append((L, 128, max(2, L // 128 // 4), "M:m = 4:1"))
+    else:
+        for B, m in ((64, 128), (128, 64), (256, 32), (512, 16), (1024, 8), (2048, 4)):
+            shapes.append((65536, B, m, "m*B = 8192"))
+        shapes.append((65536, 128, 16, "Block-Sparse shape (Stage 1 only is timed as block_sparse_ms)"))
+    for i, (L, B, m, note) in enumerate(shapes):
+        k = min(2048, m * B)
+        wl = W.make_workload(f"sweep_{a.sweep}_{L}_{B}_{m}", seq_len=L, T=1024, H=64, d=128, B=B, m=m, k=k,
+                             q_dtype=W.BF16, k_dtype=W.BF16, seed=W.BASE_SEED + 100 + i)
+        Q, K = hisa.to_device(wl)
+        pd = hisa.DTYPE_CODE[wl.pooled_dtype]
+        dev = Q.q.device
+        pooled = hisa.hisa_pool_blocks(K, B, pooled_dtype=pd)
+        block_idx = torch.empty((wl.T, m), dtype=torch.int32, device=dev)
+        topk_idx = torch.empty((wl.T, k), dtype=torch.int32, device=dev)
+        flat_idx = torch.empty((wl.T, k), dtype=torch.int32, device=dev)
+        tokens = torch.empty((wl.T, m * B), dtype=torch.int32, device=dev)
+        ws1 = torch.empty(max(1, hisa.hisa_workspace_bytes(hisa.OP_BLOCK_SCORE_TOPK, Q, K, B, m, k)),
+                          dtype=torch.uint8, device=dev)
+        ws2 = torch.empty(max(1, hisa.hisa_workspace_bytes(hisa.OP_TOKEN_REFINE_TOPK, Q, K, B, m, k)),
+                          dtype=torch.uint8, device=dev)
+        wsf = torch.empty(hisa.hisa_workspace_bytes(hisa.OP_FLAT_TOPK, Q, K, 1, 0, k), dtype=torch.uint8, device=dev)
+
+        def s1():
+            hisa.hisa_block_score_topk(Q, K, pooled, pd, B, m, block_idx=block_idx, ws=ws1)
+
+        def s2():
+            hisa.hisa_token_refine_topk(Q, K, B, m, block_idx, k, topk_idx=topk_idx, ws=ws2)
+
+        def bs():
+            s1()
+            hisa.hisa_block_sparse_tokens(Q, K, B, m, block_idx, tokens=tokens)
+
+        def flat():
+            hisa.dsa_flat_indexer_topk(Q, K, k, topk_idx=flat_idx, ws=wsf)
+
+        ms1, _ = time_region(s1, a.steps, a.warmup)
+        ms2, _ = time_region(s2, a.steps, a.warmup)
+        msb, _ = time_region(bs, a.steps, a.warmup)
+        msf, _ = time_region(flat, a.steps, a.warmup)
+        iou = float(hisa.hisa_index_iou(topk_idx, flat_idx).mean().item())
+        print(json.dumps({"sweep": a.sweep, "L": L, "T": wl.T, "B": B, "m": m, "k": k, "note": note,
+                          "stage1_ms": ms1, "stage2_ms": ms2, "hisa_ms": ms1 + ms2, "block_sparse_ms": msb,
+                          "flat_ms": msf, "flat_over_hisa": msf / (ms1 + ms2), "iou_hisa_vs_flat_mean": iou,
+                          "steps": a.steps, "warmup": a.warmup}), flush=True)
+        del Q, K, pooled, ws1, ws2, wsf, tokens
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="prefill64k_bf16")
     ap.add_argument("--flat-steps", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-flat", action="store_true")
+    ap.add_argument("--sweep", choices=["context", "blocks"], default=None,
+                    help="instead of the headline line, time the shapes of the paper's kernel-latency "
+                         "figure (Sec. 5.1: 1024 queries at the end of 8K-64K contexts, m = 64 and M:m = 4:1) "
+                         "or of its block-size ablation (App. C: (B, m) at m*B = 8192, and Block-Sparse "
+                         "(128, 16)); one JSON line per shape")
     ap.add_argument("--profile-mode", action="store_true",
                     help="for rocprofv3: run the step a few times plus a 256 MiB device copy (counter "
                          "calibration), print nothing else and exit")
@@ -129,6 +204,9 @@ def main():
 
     hisa.lib()                                  # fail loudly if the HIP library is not built
     torch.cuda.set_device(0)
+    if a.sweep:
+        sweep(a, torch, hisa, W)
+        return
     wl = W.config(a.workload)
     Q, K = hisa.to_device(wl)
     pd = hisa.DTYPE_CODE[wl.pooled_dtype]
@@ -219,10 +297,10 @@ def main():
                        "tflops": pf * flop_pair / (ms_flat * 1e-3) / 1e12,
                        "frac_of_mfma_peak": pf * flop_pair / (ms_flat * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
         out["speedup_vs_flat"] = ms_flat / ms_step
-        a_idx, b_idx = topk_idx.cpu().numpy(), flat_idx.cpu().numpy()
-        rng = np.random.default_rng(0)
-        out["iou_hisa_vs_flat_sampled"] = float(np.mean([_iou(a_idx[t], b_idx[t])
-                                                         for t in rng.choice(T, size=min(T, 512), replace=False)]))
+        # Eq. 12 over every query, computed by the library's own diagnostic kernel
+        out["iou_hisa_vs_flat_mean"] = float(hisa.hisa_index_iou(topk_idx, flat_idx).mean().item())
+        if wl.needles:
+            out["needles"] = needle_recall(wl, block_idx, topk_idx, flat_idx)
         del ws_f
 
     if not a.no_cpu_baseline:

@@ -36,6 +36,14 @@ def test_block_sizes(B, m, k):
     _run(wl, queries=sample_queries(wl, 200))
 
 
+@pytest.mark.parametrize("B,m", [(64, 128), (512, 16), (2048, 4)])
+def test_ablation_block_shapes_at_fixed_candidate_budget(B, m):
+    # Appendix C: (B, m) pairs with m*B = 8192 and k = 2048; 512 queries at the end of a 24K prefix
+    wl = W.make_workload(f"abl_B{B}", seq_len=24576, T=512, H=64, d=128, B=B, m=m, k=2048, q_dtype="bf16",
+                         k_dtype="bf16", seed=140 + m)
+    _run(wl, queries=sample_queries(wl, 48))
+
+
 def test_32_heads_and_fp8():
     wl = W.make_workload("H32", seq_len=900, T=900, H=32, d=128, B=128, m=3, k=300, q_dtype="bf16",
                          k_dtype="fp8_e4m3", seed=103)
