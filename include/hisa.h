@@ -130,8 +130,10 @@ int hisa_token_refine_topk(const hisa_queries* queries, const hisa_keys* keys, i
 
 /*
  * Flat DSA indexer (Eqs. 1-2): scores every visible key s <= q_pos and selects the k best.
- * Same outputs as Stage 2.  Queries are processed in chunks sized to the workspace:
- * minimum 8 * round_up(s_max, 64) floats (+ the merge area, see hisa_workspace_bytes).
+ * Same outputs as Stage 2.  The scores of a chunk of queries go through the workspace (one row of
+ * round_up(s_max, 64) floats per query) and are selected row by row; the library loops over
+ * chunks sized to the workspace: minimum 8 rows (plus, only for k > 2048 with s_max > 65536,
+ * 8 * k bytes per 65536-entry segment and query; hisa_workspace_bytes gives the size to pass).
  */
 int dsa_flat_indexer_topk(const hisa_queries* queries, const hisa_keys* keys, int32_t k,
                           int32_t* topk_idx, float* topk_scores, void* ws, size_t ws_bytes,

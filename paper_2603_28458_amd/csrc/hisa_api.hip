@@ -188,10 +188,14 @@ struct FlatPlan {
   long per_query;   // workspace bytes per query in a chunk
 };
 
+// Rows longer than 16384 entries with k <= 2048 go through the streaming select, which takes a
+// row of any length whole; other rows are selected from registers, in segments above 65536.
+bool flat_streams(const hisa_keys* k, int kk) { return k->s_max > 16384 && kk <= StreamSelect::kMaxK; }
+
 FlatPlan flat_plan(const hisa_keys* k, int kk) {
   FlatPlan p;
   p.ld = round_up(k->s_max, 64);
-  p.seg_len = flat_seg_len(k->s_max, kk);
+  p.seg_len = flat_streams(k, kk) ? k->s_max : flat_seg_len(k->s_max, kk);
   p.n_seg = (int)((k->s_max + p.seg_len - 1) / p.seg_len);
   p.per_query = p.ld * 4 + (p.n_seg > 1 ? (long)p.n_seg * kk * 8 : 0);
   return p;
@@ -465,7 +469,15 @@ int dsa_flat_indexer_topk(const hisa_queries* queries, const hisa_keys* keys, in
     sa.ld = p.ld;
     sa.t_begin = (int)t0;
     sa.k = k;
-    if (p.n_seg == 1) {
+    if (flat_streams(keys, k)) {
+      sa.out_idx = topk_idx + t0 * k;
+      sa.out_scores = topk_scores ? topk_scores + t0 * k : nullptr;
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_stream),
+                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                              StreamSelect::kBytes) != hipSuccess)
+        return HISA_ERR_LAUNCH;
+      hipLaunchKernelGGL(k_select_stream, dim3(1, tc), dim3(StreamSelect::kThreads), StreamSelect::kBytes, s, sa);
+    } else if (p.n_seg == 1) {
       sa.out_idx = topk_idx + t0 * k;
       sa.out_scores = topk_scores ? topk_scores + t0 * k : nullptr;
       st = launch_select<MAP_FLAT>(sa, tc, keys->s_max, s);

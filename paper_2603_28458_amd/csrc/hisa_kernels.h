@@ -665,6 +665,362 @@ __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Streaming exact top-k of one long score row (flat indexer, Eq. 2; k <= 2048).  The row stays in
+// global memory and is read a few times instead of being held in registers:
+//   1. a sample of the row gives a key range [rlo, rhi];
+//   2. one pass histograms the keys into 4096 bins: bin 0 below rlo, bins 1..4094 equal slices of
+//      the range, bin 4095 above it (any monotone binning keeps the selection exact; the range
+//      only spreads the keys, so that the LDS atomics rarely collide);
+//   3. the bin that holds the k-th key is found; if it holds more keys than the candidate list
+//      can take, steps 2-3 repeat inside that bin's key range (only for degenerate rows);
+//   4. one pass in index order collects the indices above the bin (selected for sure) and the
+//      (index, key) pairs inside it; select_topk picks the missing r among those; both lists are
+//      ascending and are merged into the output by rank.
+// Order: key descending, then index ascending; output ascending, -1 padding.
+struct StreamSelect {
+  static constexpr int kThreads = 1024, kBins = 4096, kCap = 4 * kThreads, kMaxK = 2048;
+  static constexpr int kHist = 0;                                   // uint32 [kBins]; later the winners
+  static constexpr int kSure = kBins * 4;                           // int32 idx [kMaxK], uint32 key [kMaxK]
+  static constexpr int kCand = kSure + kMaxK * 8;                   // int32 idx [kCap], uint32 key [kCap]
+  static constexpr int kSel = kCand + kCap * 8;                     // SelectSmem<kThreads, 4>
+  static constexpr int kTot = kSel + (int)((sizeof(SelectSmem<kThreads, 4>) + 15) / 16 * 16);
+  static constexpr int kBytes = kTot + 2 * (kThreads / 64) * 4 + 64;   // chunk totals [2][waves] + broadcast
+};
+
+__global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(SelectArgs a) {
+  using P = StreamSelect;
+  constexpr int THREADS = P::kThreads, NW = THREADS / 64, NBIN = P::kBins, CAP = P::kCap;
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint32_t* hist = reinterpret_cast<uint32_t*>(smem + P::kHist);
+  int32_t* win_idx = reinterpret_cast<int32_t*>(smem + P::kHist);   // aliases hist (dead by then)
+  uint32_t* win_key = reinterpret_cast<uint32_t*>(smem + P::kHist + P::kMaxK * 4);
+  int32_t* sure_idx = reinterpret_cast<int32_t*>(smem + P::kSure);
+  uint32_t* sure_key = reinterpret_cast<uint32_t*>(smem + P::kSure + P::kMaxK * 4);
+  int32_t* cand_idx = reinterpret_cast<int32_t*>(smem + P::kCand);
+  uint32_t* cand_key = reinterpret_cast<uint32_t*>(smem + P::kCand + CAP * 4);
+  SelectSmem<THREADS, 4>& sm = *reinterpret_cast<SelectSmem<THREADS, 4>*>(smem + P::kSel);
+  uint32_t* tot = reinterpret_cast<uint32_t*>(smem + P::kTot);      // [2][NW]
+  uint32_t* bc = tot + 2 * NW;                                      // broadcast words
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row = blockIdx.y;
+  const int t = a.t_begin + row;
+  int sq = a.q_seq ? a.q_seq[t] : 0;
+  sq = sq < 0 ? 0 : (sq >= a.n_seq ? a.n_seq - 1 : sq);
+  int pos = a.q_pos ? a.q_pos[t] : a.q_pos0 + t;
+  const int sl = a.seq_len[sq];
+  pos = pos < sl ? pos : sl - 1;
+  const int n = pos < 0 ? 0 : pos + 1;
+  const int k = a.k;
+  const float* rowp = a.scores + (long)row * a.ld;
+  int32_t* oi = a.out_idx + (long)row * k;
+  float* os = a.out_scores ? a.out_scores + (long)row * k : nullptr;
+
+  if (n <= 0) {
+    for (int p = tid; p < k; p += THREADS) {
+      oi[p] = -1;
+      if (os) os[p] = neg_inf();
+    }
+    return;
+  }
+  if (n <= k) {   // Section 4.1, boundary behaviour: a prefix no longer than k is selected whole
+    int bad = 0;   // a -inf entry is not a candidate: such a row takes the general path below
+    for (int p = tid; p < n; p += THREADS) bad |= rowp[p] == neg_inf();
+    if (!__syncthreads_or(bad)) {
+      for (int p = tid; p < k; p += THREADS) {
+        oi[p] = p < n ? p : -1;
+        if (os) os[p] = p < n ? rowp[p] : neg_inf();
+      }
+      return;
+    }
+  }
+
+  // The row through a buffer descriptor of exactly n floats: a 16-byte load needs no branch at
+  // the ragged end (bytes past the row read as zero and are masked by index below).
+  const __amdgpu_buffer_rsrc_t rrow = key_buffer(rowp, (long)n * 4);
+  auto raw4 = [&](int i) -> u32x4v { return __builtin_amdgcn_raw_buffer_load_b128(rrow, i * 4, 0, 0); };
+  // keys of elements i .. i+3 (0 = not a candidate: beyond the row, or a -inf score)
+  auto keys_of = [&](int i, const u32x4v& r, uint32_t (&kk)[4]) {
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const uint32_t key = ordered_key(__uint_as_float(r[x]));
+      kk[x] = (i + x < n) ? key : 0u;
+    }
+  };
+
+  // 1. key range of a sample
+  uint32_t kmin = 0xffffffffu, kmax = 1u;
+  {
+    // up to 4096 entries at a constant stride (wave-uniform arithmetic, four loads in flight)
+    const int stride = n > 4 * THREADS ? n / (4 * THREADS) : 1;
+    float sv[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const long j = (long)(tid * 4 + x) * stride;
+      sv[x] = j < n ? rowp[j] : neg_inf();
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const uint32_t key = ordered_key(sv[x]);
+      if (key) {
+        kmin = key < kmin ? key : kmin;
+        kmax = key > kmax ? key : kmax;
+      }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const uint32_t lo = __shfl_xor(kmin, off), hi = __shfl_xor(kmax, off);
+      kmin = lo < kmin ? lo : kmin;
+      kmax = hi > kmax ? hi : kmax;
+    }
+    if (lane == 0) {
+      tot[wave] = kmin;
+      tot[NW + wave] = kmax;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int v = 0; v < NW; ++v) {
+      kmin = tot[v] < kmin ? tot[v] : kmin;
+      kmax = tot[NW + v] > kmax ? tot[NW + v] : kmax;
+    }
+    if (kmin > kmax) kmin = kmax;
+    kmin = __builtin_amdgcn_readfirstlane(kmin);   // workgroup-uniform from here on: scalar registers
+    kmax = __builtin_amdgcn_readfirstlane(kmax);
+    __syncthreads();
+  }
+
+  // 2.-3. histogram levels
+  uint32_t plo = 1u, phi = 0xffffffffu;   // exact key range that still holds the k-th key
+  uint32_t rlo = kmin, rhi = kmax;        // range the bins 1 .. NBIN-2 are laid over
+  uint32_t krem = (uint32_t)k;            // how many keys to take from [plo, phi]
+  uint32_t n_c = 0;                       // keys inside [plo, phi]
+  bool all_valid = false;                 // fewer than k candidates: every candidate is selected
+  for (int level = 0; level < 8; ++level) {
+    int shift = 0;
+    while (((rhi - rlo) >> shift) > (uint32_t)(NBIN - 3)) ++shift;
+    const unsigned long long top = (unsigned long long)rlo + ((unsigned long long)(NBIN - 2) << shift) - 1ull;
+    const uint32_t rhi_eff = top > 0xffffffffull ? 0xffffffffu : (uint32_t)top;
+    for (int b = tid; b < NBIN; b += THREADS) hist[b] = 0u;
+    __syncthreads();
+    // four 16-byte loads in flight per thread before their keys are binned
+    for (int i0 = tid * 4; i0 < n; i0 += THREADS * 16) {
+      u32x4v q[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) q[u] = raw4(i0 + u * THREADS * 4);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        uint32_t kk[4];
+        keys_of(i0 + u * THREADS * 4, q[u], kk);
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          const uint32_t key = kk[x];
+          if (key >= plo && key <= phi) {
+            const uint32_t bin =
+                key < rlo ? 0u : (key > rhi_eff ? (uint32_t)(NBIN - 1) : ((key - rlo) >> shift) + 1u);
+            atomicAdd(&hist[bin], 1u);
+          }
+        }
+      }
+    }
+    __syncthreads();
+    // suffix sums over the bins: thread t owns bins 4t .. 4t+3
+    static_assert(NBIN == 4 * THREADS, "four bins per thread");
+    const uint32_t c0 = hist[4 * tid + 0], c1 = hist[4 * tid + 1], c2 = hist[4 * tid + 2], c3 = hist[4 * tid + 3];
+    const uint32_t mine = c0 + c1 + c2 + c3;
+    uint32_t S = mine;   // inclusive suffix sum over the lanes of the wave
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t v = __shfl_down(S, off);
+      if (lane + off < 64) S += v;
+    }
+    if (lane == 0) tot[wave] = S;
+    __syncthreads();
+    uint32_t total = 0;
+#pragma unroll
+    for (int v = 0; v < NW; ++v) {
+      const uint32_t tv = tot[v];
+      total += tv;
+      if (v > wave) S += tv;
+    }
+    total = __builtin_amdgcn_readfirstlane(total);
+    if (level == 0 && total <= krem) {
+      all_valid = true;
+      __syncthreads();
+      break;
+    }
+    const uint32_t a3 = S - mine, a2 = a3 + c3, a1 = a2 + c2, a0 = a1 + c1;
+    int dsel = -1;
+    uint32_t above = 0, cnt = 0;
+    if (a3 < krem && krem <= a3 + c3) { dsel = 3; above = a3; cnt = c3; }
+    if (a2 < krem && krem <= a2 + c2) { dsel = 2; above = a2; cnt = c2; }
+    if (a1 < krem && krem <= a1 + c1) { dsel = 1; above = a1; cnt = c1; }
+    if (a0 < krem && krem <= a0 + c0) { dsel = 0; above = a0; cnt = c0; }
+    if (dsel >= 0) {
+      bc[0] = (uint32_t)(4 * tid + dsel);
+      bc[1] = krem - above;
+      bc[2] = cnt;
+    }
+    __syncthreads();
+    const uint32_t bsel = __builtin_amdgcn_readfirstlane(bc[0]);
+    krem = __builtin_amdgcn_readfirstlane(bc[1]);
+    n_c = __builtin_amdgcn_readfirstlane(bc[2]);
+    uint32_t nlo, nhi;
+    if (bsel == 0u) {
+      nlo = plo;
+      nhi = rlo - 1u;   // bin 0 is non-empty, so rlo > plo >= 1
+    } else if (bsel == (uint32_t)(NBIN - 1)) {
+      nlo = rhi_eff + 1u;   // bin NBIN-1 is non-empty, so rhi_eff < 0xffffffff
+      nhi = phi;
+    } else {
+      nlo = rlo + ((bsel - 1u) << shift);
+      nhi = nlo + ((1u << shift) - 1u);
+    }
+    plo = nlo > plo ? nlo : plo;
+    phi = nhi < phi ? nhi : phi;
+    __syncthreads();   // bc and tot are reused
+    if (n_c <= (uint32_t)CAP || plo == phi) break;
+    rlo = plo;
+    rhi = phi;
+  }
+  // Keys above phi are selected for sure.  Keys in [plo, phi]: krem of them are selected; if they
+  // do not fit the list they are all equal (plo == phi) and the first krem in index order win.
+  const bool equal_mode = !all_valid && n_c > (uint32_t)CAP;
+  const uint32_t r = all_valid ? 0u : krem;
+  const uint32_t sure_lo = all_valid ? 1u : phi + 1u;   // phi + 1 == 0 means: none (phi = 0xffffffff)
+
+  // 4. collect in index order
+  uint32_t base_s = 0, base_c = 0;
+  int par = 0;
+  // the loads of the next two chunks fly over this chunk's scan
+  u32x4v q_a = raw4(tid * 4), q_b = raw4(tid * 4 + THREADS * 4);
+  for (int c0 = 0; c0 < n; c0 += THREADS * 4) {
+    const int i = c0 + tid * 4;
+    const u32x4v q = q_a;
+    q_a = q_b;
+    q_b = raw4(i + THREADS * 8);
+    uint32_t kk[4];
+    keys_of(i, q, kk);
+    bool is_s[4], is_c[4];
+    uint32_t cs = 0, cc = 0;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const uint32_t key = kk[x];
+      is_s[x] = key != 0u && sure_lo != 0u && key >= sure_lo;
+      is_c[x] = !all_valid && key >= plo && key <= phi;
+      cs += is_s[x];
+      cc += is_c[x];
+    }
+    const uint32_t packed = cs | (cc << 16);
+    uint32_t inc = packed;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t v = __shfl_up(inc, off);
+      if (lane >= off) inc += v;
+    }
+    if (lane == 63) tot[par * NW + wave] = inc;
+    __syncthreads();
+    uint32_t before = 0, chunk = 0;
+#pragma unroll
+    for (int v = 0; v < NW; ++v) {
+      const uint32_t tv = tot[par * NW + v];
+      chunk += tv;
+      if (v < wave) before += tv;
+    }
+    uint32_t ps = base_s + (before & 0xffffu) + (inc & 0xffffu) - cs;
+    uint32_t pc = base_c + (before >> 16) + (inc >> 16) - cc;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      if (is_s[x]) {
+        if (ps < (uint32_t)P::kMaxK) {
+          sure_idx[ps] = i + x;
+          sure_key[ps] = kk[x];
+        }
+        ++ps;
+      }
+      if (is_c[x]) {
+        if (equal_mode) {
+          if (pc < r) {
+            win_idx[pc] = i + x;
+            win_key[pc] = kk[x];
+          }
+        } else if (pc < (uint32_t)CAP) {
+          cand_idx[pc] = i + x;
+          cand_key[pc] = kk[x];
+        }
+        ++pc;
+      }
+    }
+    base_s += __builtin_amdgcn_readfirstlane(chunk & 0xffffu);
+    base_c += __builtin_amdgcn_readfirstlane(chunk >> 16);
+    par ^= 1;   // the next chunk writes the other totals row: one barrier per chunk is enough
+  }
+  __syncthreads();
+  const int n_s = (int)(base_s < (uint32_t)P::kMaxK ? base_s : (uint32_t)P::kMaxK);
+
+  // the r best of the candidate list (ascending index in, ascending index out)
+  int n_w = (int)r;
+  const int nc_all = (int)(base_c < (uint32_t)CAP ? base_c : (uint32_t)CAP);
+  if (!equal_mode && r > 0u && nc_all <= THREADS) {
+    // the usual case, a short list: one candidate per thread, ranked by counting the candidates
+    // that beat it (larger key, or equal key earlier in the list); no radix passes
+    uint32_t* flag = reinterpret_cast<uint32_t*>(&sm);   // [THREADS] selected flags
+    const uint32_t mykey = tid < nc_all ? cand_key[tid] : 0u;
+    uint32_t rank = 0;
+    for (int j = 0; j < nc_all; ++j) {
+      const uint32_t kj = cand_key[j];
+      rank += (kj > mykey) || (kj == mykey && j < tid);
+    }
+    const bool sel = tid < nc_all && rank < r;
+    flag[tid] = sel ? 1u : 0u;
+    __syncthreads();
+    if (sel) {
+      uint32_t before = 0;
+      for (int j = 0; j < tid; ++j) before += flag[j];
+      win_idx[before] = cand_idx[tid];
+      win_key[before] = mykey;
+    }
+    n_w = (int)(r < (uint32_t)nc_all ? r : (uint32_t)nc_all);
+  } else if (!equal_mode && r > 0u) {
+    const int nc = nc_all;
+    auto load4 = [&](int q4) -> uint4 { return *reinterpret_cast<const uint4*>(cand_key + 4 * q4); };
+    auto load1 = [&](int i) -> uint32_t { return cand_key[i]; };
+    auto emit = [&](int p, int i, uint32_t key) {
+      win_idx[p] = cand_idx[i];
+      win_key[p] = key;
+    };
+    n_w = select_topk<THREADS, 4>(sm, nc, (int)r, load4, load1, emit);
+  }
+  __syncthreads();
+
+  // merge the two ascending lists by rank
+  auto lower_bound = [](const int32_t* v, int len, int x) -> int {
+    int lo = 0, hi = len;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (v[mid] < x) lo = mid + 1;
+      else hi = mid;
+    }
+    return lo;
+  };
+  for (int j = tid; j < n_s; j += THREADS) {
+    const int x = sure_idx[j];
+    const int p = j + lower_bound(win_idx, n_w, x);
+    oi[p] = x;
+    if (os) os[p] = key_to_score(sure_key[j]);
+  }
+  for (int j = tid; j < n_w; j += THREADS) {
+    const int y = win_idx[j];
+    const int p = j + lower_bound(sure_idx, n_s, y);
+    oi[p] = y;
+    if (os) os[p] = key_to_score(win_key[j]);
+  }
+  for (int p = n_s + n_w + tid; p < k; p += THREADS) {
+    oi[p] = -1;
+    if (os) os[p] = neg_inf();
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // Stage 2 fused (Eqs. 7-9): one workgroup of NW waves per query scores every tile of the kept
 // blocks into LDS and selects the top k there; only the k indices leave the CU.  E = candidates
 // per thread in the select (NW * 64 * E >= m * B).  LDS: the per-wave tile rings, then the m*B
