@@ -189,6 +189,8 @@ def main():
                          "figure (Sec. 5.1: 1024 queries at the end of 8K-64K contexts, m = 64 and M:m = 4:1) "
                          "or of its block-size ablation (App. C: (B, m) at m*B = 8192, and Block-Sparse "
                          "(128, 16)); one JSON line per shape")
+    ap.add_argument("--profile-flat", action="store_true",
+                    help="with --profile-mode: run the flat DSA indexer instead of the HISA step")
     ap.add_argument("--profile-mode", action="store_true",
                     help="for rocprofv3: run the step a few times plus a 256 MiB device copy (counter "
                          "calibration), print nothing else and exit")
@@ -240,8 +242,14 @@ def main():
 
     pool()
     if a.profile_mode:
-        for _ in range(max(1, a.steps)):
-            step()
+        if a.profile_flat:
+            ws_f = torch.empty(hisa.hisa_workspace_bytes(hisa.OP_FLAT_TOPK, Q, K, 1, 0, wl.k), dtype=torch.uint8,
+                               device=dev)
+            for _ in range(max(1, a.steps)):
+                hisa.dsa_flat_indexer_topk(Q, K, wl.k, topk_idx=topk_idx, ws=ws_f)
+        else:
+            for _ in range(max(1, a.steps)):
+                step()
         src = torch.ones(64 << 20, dtype=torch.float32, device=dev)     # 256 MiB read + 256 MiB written
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
@@ -270,6 +278,19 @@ def main():
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["ms_per_launch"] = ms_s2
     roof["traffic"] = measured_traffic(a.workload)
+    # what this chip delivers to a kernel that does nothing else: a 1 GiB streaming copy and a loop
+    # of MFMAs only (the library's probe kernels), for the fraction of the ATTAINABLE peak
+    src = torch.empty(1 << 29, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    ms_copy, _ = time_region(lambda: hisa.hisa_probe_copy(src, dst), 5, 1)
+    probe_out = torch.empty(512 * 256, dtype=torch.float32, device=dev)
+    flop_box = []
+    ms_mfma, _ = time_region(lambda: flop_box.append(hisa.hisa_probe_mfma(probe_out, 20000)), 3, 1)
+    attainable = {"hbm_copy_GBs": 2.0 * src.numel() / (ms_copy * 1e-3) / 1e9,
+                  "mfma_bf16_TFLOPs": flop_box[-1] / (ms_mfma * 1e-3) / 1e12}
+    del src, dst
+    roof["frac_of_attainable"] = roof["achieved"] / (attainable["hbm_copy_GBs"] if roof["bound"] == "hbm"
+                                                     else attainable["mfma_bf16_TFLOPs"])
 
     out = {
         "metric": "indexer queries/s at 64K context (HISA: pool + Stage 1 + Stage 2)" if "64k" in a.workload
@@ -283,6 +304,7 @@ def main():
         "algorithmic": {"stage1_pairs": p1, "stage2_pairs": p2, "flat_pairs": pf, "flop_per_pair": flop_pair,
                         "hisa_tflop": (p1 + p2) * flop_pair / 1e12, "flat_tflop": pf * flop_pair / 1e12},
         "roofline": roof,
+        "attainable": attainable,
     }
 
     if not a.no_flat:

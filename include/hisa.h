@@ -171,6 +171,17 @@ int hisa_block_sparse_tokens(const hisa_queries* queries, const hisa_keys* keys,
 int hisa_index_iou(const int32_t* a_idx, const int32_t* b_idx, int32_t T, int32_t k, float* iou,
                    void* stream);
 
+/*
+ * Attainable-peak probes for benchmarks (measurement aids; nothing of the paper's method).
+ * hisa_probe_copy: one streaming device-to-device copy of `bytes` (a multiple of 16; both pointers
+ * device, 16-byte aligned) with a 4096-workgroup grid: bytes read + bytes written over its time is
+ * the HBM rate this chip sustains.  hisa_probe_mfma: 512 workgroups of 4 waves each issue
+ * iters * 16 v_mfma_f32_32x32x16_bf16 and nothing else; *flop (host) receives the flop count of the
+ * launch, out (device, 512 * 256 floats) receives values that only keep the loop alive.
+ */
+int hisa_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+int hisa_probe_mfma(float* out, int32_t iters, double* flop, void* stream);
+
 /* Recommended workspace size in bytes for `op` (HISA_OP_*) at these shapes; 0 if none is needed
  * or the shapes are invalid.  `want_scores` != 0: the optional full score output of Stage 1 / 2
  * is requested (which then replaces the workspace). */

@@ -310,6 +310,24 @@ int hisa_index_iou(const int32_t* a_idx, const int32_t* b_idx, int32_t T, int32_
   return launch_status();
 }
 
+int hisa_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (!src || !dst) return HISA_ERR_NULL;
+  if (bytes < 16 || bytes % 16) return HISA_ERR_SHAPE;
+  if (!aligned16(src) || !aligned16(dst)) return HISA_ERR_ALIGN;
+  hipLaunchKernelGGL(k_probe_copy, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream, (const uint4*)src,
+                     (uint4*)dst, (long)(bytes / 16));
+  return launch_status();
+}
+
+int hisa_probe_mfma(float* out, int32_t iters, double* flop, void* stream) {
+  if (!out || !flop) return HISA_ERR_NULL;
+  if (iters < 1) return HISA_ERR_SHAPE;
+  const int wgs = 512;   // two 4-wave workgroups per CU: two waves per SIMD
+  hipLaunchKernelGGL(k_probe_mfma, dim3(wgs), dim3(256), 0, (hipStream_t)stream, out, iters);
+  *flop = (double)wgs * 4.0 * iters * 16.0 * (2.0 * 32 * 32 * 16);
+  return launch_status();
+}
+
 int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, const void* pooled,
                           int32_t pooled_dtype, int32_t B, int32_t m, int32_t* block_idx,
                           float* block_scores, void* ws, size_t ws_bytes, void* stream) {

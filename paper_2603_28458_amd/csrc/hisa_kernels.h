@@ -199,6 +199,44 @@ __global__ __launch_bounds__(256) void k_index_iou(const int32_t* __restrict__ a
 }
 
 // ------------------------------------------------------------------------------------------
+// Attainable-peak probes (measurement aids, not part of the method): a streaming copy and a loop
+// of nothing but MFMAs, so that a benchmark can quote its kernels against what this chip delivers.
+__global__ __launch_bounds__(256) void k_probe_copy(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                    long n16) {
+  // four 16-byte loads in flight per thread
+  const long stride = (long)gridDim.x * 256;
+  long i = (long)blockIdx.x * 256 + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a;
+    dst[i + stride] = b;
+    dst[i + 2 * stride] = c;
+    dst[i + 3 * stride] = d;
+  }
+  for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void k_probe_mfma(float* out, int iters) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    a[e] = (__bf16)(float)(threadIdx.x & 3);
+    b[e] = (__bf16)(float)(threadIdx.x & 1);
+  }
+  f32x16 acc[4];
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[n][i] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int n = 0; n < 4; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[n], 0, 0, 0);
+  }
+  out[(long)blockIdx.x * 256 + threadIdx.x] = (acc[0][0] + acc[1][5]) + (acc[2][9] + acc[3][15]);
+}
+
 __global__ __launch_bounds__(256) void k_fill_f32(float* p, long n, float v) {
   for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long)gridDim.x * 256) p[i] = v;
 }
@@ -751,13 +789,15 @@ __global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(Sel
   // 1. key range of a sample
   uint32_t kmin = 0xffffffffu, kmax = 1u;
   {
-    // up to 4096 entries at a constant stride (wave-uniform arithmetic, four loads in flight)
-    const int stride = n > 4 * THREADS ? n / (4 * THREADS) : 1;
+    // up to 4096 entries: 64 evenly spaced runs of 64 consecutive entries (16 KB of the row;
+    // single entries at a constant stride would pull in nearly every line of it)
+    const int run_stride = n > 4 * THREADS ? n >> 6 : 64;
     float sv[4];
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
-      const long j = (long)(tid * 4 + x) * stride;
-      sv[x] = j < n ? rowp[j] : neg_inf();
+      const int j = tid * 4 + x;
+      const long idx = (long)(j >> 6) * run_stride + (j & 63);
+      sv[x] = idx < n ? rowp[idx] : neg_inf();
     }
 #pragma unroll
     for (int x = 0; x < 4; ++x) {

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libh
 
 EXPORTS = ["hisa_pool_blocks", "hisa_pool_append", "hisa_block_score_topk", "hisa_token_refine_topk",
            "hisa_block_sparse_tokens", "hisa_index_iou", "dsa_flat_indexer_topk", "hisa_workspace_bytes",
-           "hisa_status_string", "hisa_version"]
+           "hisa_status_string", "hisa_version", "hisa_probe_copy", "hisa_probe_mfma"]
 
 
 class HisaError(RuntimeError):
@@ -71,6 +71,10 @@ def lib() -> C.CDLL:
         L.hisa_workspace_bytes.argtypes = [C.c_int, C.POINTER(_Queries), C.POINTER(_Keys), i32, i32,
                                            i32, i32]
         L.hisa_workspace_bytes.restype = sz
+        L.hisa_probe_copy.argtypes = [vp, vp, sz, vp]
+        L.hisa_probe_copy.restype = C.c_int
+        L.hisa_probe_mfma.argtypes = [vp, i32, C.POINTER(C.c_double), vp]
+        L.hisa_probe_mfma.restype = C.c_int
         L.hisa_status_string.argtypes = [C.c_int]
         L.hisa_status_string.restype = C.c_char_p
         L.hisa_version.argtypes = []
@@ -275,6 +279,22 @@ def dsa_flat_indexer_topk(queries: Queries, keys: Keys, k: int, topk_idx: Option
                                      _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream))
     _check(st, "dsa_flat_indexer_topk")
     return topk_idx, topk_scores
+
+
+def hisa_probe_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> int:
+    """Streaming copy probe; returns the bytes moved (read + written)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(lib().hisa_probe_copy(_ptr(src), _ptr(dst), nbytes, _stream(stream)), "hisa_probe_copy")
+    return 2 * nbytes
+
+
+def hisa_probe_mfma(out: torch.Tensor, iters: int, stream=None) -> float:
+    """MFMA-only probe; `out` holds at least 512 * 256 floats; returns the flop count of the launch."""
+    assert out.dtype == torch.float32 and out.numel() >= 512 * 256
+    flop = C.c_double(0.0)
+    _check(lib().hisa_probe_mfma(_ptr(out), iters, C.byref(flop), _stream(stream)), "hisa_probe_mfma")
+    return flop.value
 
 
 # ---------------------------------------------------------------- moving a workload to the GPU

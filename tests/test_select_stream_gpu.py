@@ -77,9 +77,9 @@ def test_few_distinct_values_with_ties_at_the_threshold():
 
 
 def _sampled_indices(n):
-    # the select samples up to 4096 entries at stride n // 4096 (1 for short rows)
-    stride = n // 4096 if n > 4096 else 1
-    return {j * stride for j in range(4096) if j * stride < n}
+    # the select samples up to 4096 entries: 64 evenly spaced runs of 64 consecutive entries
+    run_stride = n >> 6 if n > 4096 else 64
+    return {(j >> 6) * run_stride + (j & 63) for j in range(4096) if (j >> 6) * run_stride + (j & 63) < n}
 
 
 def test_threshold_above_the_sampled_range():
