@@ -197,7 +197,7 @@ def main():
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the indexer shards by query with no exchange; "
-              "see DESIGN.md); --gpus above 1 is not supported", file=sys.stderr)
+              "nothing is exchanged between GPUs); --gpus above 1 is not supported", file=sys.stderr)
         sys.exit(2)
 
     import torch

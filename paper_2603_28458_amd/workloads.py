@@ -132,6 +132,8 @@ def make_workload(name: str, *, n_seq: int = 1, seq_len, T: int, H: int, d: int,
     mode = "prefill": one sequence, T queries at positions seq_len-T .. seq_len-1 (T == seq_len is a
                       full causal prefill; T < seq_len is a chunk against a longer prefix).
     mode = "decode" : n_seq sequences, one query each at its sequence's last position (T == n_seq).
+    mode = "varlen" : n_seq sequences prefilled whole and packed one after the other
+                      (T == sum(seq_len); q_seq / q_pos give every query's sequence and position).
     seq_len: int, or a sequence of n_seq ints.
     """
     ss_q, ss_k, ss_misc = np.random.SeedSequence(seed).spawn(3)
@@ -162,6 +164,13 @@ def make_workload(name: str, *, n_seq: int = 1, seq_len, T: int, H: int, d: int,
         q_pos0 = 0
         q_seq = np.arange(T, dtype=np.int32)
         q_pos = (seq_len - 1).astype(np.int32)
+        pos = q_pos.astype(np.int64)
+        seqs = q_seq.astype(np.int64)
+    elif mode == "varlen":
+        assert T == int(seq_len.sum())
+        q_pos0 = 0
+        q_seq = np.repeat(np.arange(n_seq, dtype=np.int32), seq_len)
+        q_pos = np.concatenate([np.arange(int(n), dtype=np.int32) for n in seq_len])
         pos = q_pos.astype(np.int64)
         seqs = q_seq.astype(np.int64)
     else:

@@ -64,6 +64,15 @@ def test_decode_batch_ragged_lengths(k_dtype):
     _run(wl)
 
 
+@pytest.mark.parametrize("k_dtype", ["bf16", "fp8_e4m3"])
+def test_packed_varlen_prefill(k_dtype):
+    # three sequences of different lengths prefilled in one call (each starts at a block boundary
+    # of its own padded key array): per-query sequence ids and positions, fused Stage 2
+    wl = W.make_workload(f"varlen_{k_dtype}", n_seq=3, seq_len=[700, 1300, 257], T=2257, H=64, d=128, B=128,
+                         m=4, k=256, q_dtype="bf16", k_dtype=k_dtype, mode="varlen", seed=130)
+    _run(wl, queries=sample_queries(wl, 200))
+
+
 def test_fp32_generic_shapes():
     wl = W.make_workload("f32_odd", seq_len=777, T=777, H=3, d=20, B=16, m=5, k=50, q_dtype="f32", k_dtype="f32",
                          seed=106)
