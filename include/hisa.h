@@ -140,6 +140,21 @@ int dsa_flat_indexer_topk(const hisa_queries* queries, const hisa_keys* keys, in
                           void* stream);
 
 /*
+ * Algorithm 1 whole in one launch: Stage 1 (Eqs. 5-6) and Stage 2 (Eqs. 7-9) of each query run
+ * back to back in one workgroup, the query is read once, the block scores and the kept block ids
+ * never leave the CU.  Same results as hisa_block_score_topk followed by hisa_token_refine_topk.
+ *   pooled     [n_seq, s_max / B, d] BF16 (device, in), as hisa_pool_blocks writes it
+ *   block_idx  [T, m] int32 (device, out) or NULL: the kept block ids, ascending then -1
+ *   topk_idx / topk_scores: as hisa_token_refine_topk
+ * Supported: q BF16, k BF16 or FP8_E4M3, pooled BF16, d == 128, H in {32, 64}, B % 32 == 0,
+ * m * B <= 16384, s_max / B <= 8192; anything else returns HISA_ERR_SHAPE / HISA_ERR_DTYPE (use the
+ * two calls).  Needs no workspace.
+ */
+int hisa_indexer_topk(const hisa_queries* queries, const hisa_keys* keys, const void* pooled,
+                      int32_t pooled_dtype, int32_t B, int32_t m, int32_t k, int32_t* block_idx,
+                      int32_t* topk_idx, float* topk_scores, void* stream);
+
+/*
  * Incremental maintenance of the pooled-key cache (Section 4.1: the pooled keys "can be
  * incrementally maintained alongside the KV cache"; Section 4.2 assumes it).  After sequence n grew
  * from prev_len[n] to keys->seq_len[n] tokens (appended at the end), recomputes exactly the pooled

@@ -170,7 +170,8 @@ int launch_fused_hg(const ScoreArgs& a, int k, int32_t* topk_idx, float* topk_sc
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh) != hipSuccess)
     return HISA_ERR_LAUNCH;
-  hipLaunchKernelGGL(kern, dim3(a.t_count), dim3(NW * 64), sh, st, a, k, topk_idx, topk_scores);
+  hipLaunchKernelGGL(kern, dim3(a.t_count), dim3(NW * 64), sh, st, a, k, topk_idx, topk_scores,
+                     (const void*)nullptr, (int32_t*)nullptr, 0);
   return HISA_OK;
 }
 
@@ -178,6 +179,37 @@ template <int KDT, int EC>
 int launch_fused(const ScoreArgs& a, int k, int32_t* topk_idx, float* topk_scores, hipStream_t st) {
   return a.H == 64 ? launch_fused_hg<2, KDT, EC>(a, k, topk_idx, topk_scores, st)
                    : launch_fused_hg<1, KDT, EC>(a, k, topk_idx, topk_scores, st);
+}
+
+// Single-launch HISA (Stage 1 + Stage 2 in k_refine_fused): NW waves per query; the Stage 1
+// select holds E1 blocks per thread (NW * 64 * E1 >= 8192 blocks).
+template <int HG, int KDT, int NW, int EC>
+int launch_indexer_hg(const ScoreArgs& a, const void* pooled, int k, int32_t* block_idx_out,
+                      int32_t* topk_idx, float* topk_scores, hipStream_t st) {
+  constexpr int E = ((EC * 4 + NW - 1) / NW + 3) / 4 * 4;
+  constexpr int E1 = NW == 4 ? 32 : 16;
+  const int M = (int)(a.rows_per_seq / a.B);
+  const int sc_floats = (int)round_up(a.m * a.B > M ? a.m * a.B : M, 32);
+  const size_t tile = TileGeom<KDT>::kBufBytes < 8192 ? 8192 : TileGeom<KDT>::kBufBytes;
+  const size_t sh = (size_t)NW * kNBuf * tile + (size_t)sc_floats * 4 + (size_t)round_up(a.m, 4) * 4;
+  auto kern = k_refine_fused<HG, KDT, NW, kNBuf, E, E1>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh) != hipSuccess)
+    return HISA_ERR_LAUNCH;
+  hipLaunchKernelGGL(kern, dim3(a.t_count), dim3(NW * 64), sh, st, a, k, topk_idx, topk_scores, pooled,
+                     block_idx_out, sc_floats);
+  return HISA_OK;
+}
+
+template <int KDT, int NW>
+int launch_indexer(const ScoreArgs& a, const void* pooled, int k, int32_t* block_idx_out,
+                   int32_t* topk_idx, float* topk_scores, hipStream_t st) {
+  const bool big = (long)a.m * a.B > 8192;
+  if (a.H == 64)
+    return big ? launch_indexer_hg<2, KDT, NW, 64>(a, pooled, k, block_idx_out, topk_idx, topk_scores, st)
+               : launch_indexer_hg<2, KDT, NW, 32>(a, pooled, k, block_idx_out, topk_idx, topk_scores, st);
+  return big ? launch_indexer_hg<1, KDT, NW, 64>(a, pooled, k, block_idx_out, topk_idx, topk_scores, st)
+             : launch_indexer_hg<1, KDT, NW, 32>(a, pooled, k, block_idx_out, topk_idx, topk_scores, st);
 }
 
 // Flat indexer: rows of queries scored per chunk, and the size of the segment-merge area.
@@ -444,6 +476,41 @@ int hisa_token_refine_topk(const hisa_queries* queries, const hisa_keys* keys, i
   sa.out_idx = topk_idx;
   sa.out_scores = topk_scores;
   st = launch_select<MAP_CAND>(sa, T, n_slots, s);
+  if (st) return st;
+  return launch_status();
+}
+
+int hisa_indexer_topk(const hisa_queries* queries, const hisa_keys* keys, const void* pooled,
+                      int32_t pooled_dtype, int32_t B, int32_t m, int32_t k, int32_t* block_idx,
+                      int32_t* topk_idx, float* topk_scores, void* stream) {
+  int st = check_queries(queries);
+  if (st) return st;
+  st = check_keys(keys, true);
+  if (st) return st;
+  if (!pooled || !topk_idx) return HISA_ERR_NULL;
+  if (!aligned16(pooled)) return HISA_ERR_ALIGN;
+  if (B < 1 || keys->s_max % B || k < 1 || k > kMaxK || m > kMaxM) return HISA_ERR_SHAPE;
+  if (m < 2 || (long)m * B < k) return HISA_ERR_INFEASIBLE;
+  int path = pick_path(queries->q_dtype, keys->k_dtype, queries->H, keys->d, &st);
+  if (!path) return st;
+  if (path != PATH_MFMA || pooled_dtype != HISA_BF16) return HISA_ERR_DTYPE;
+  if (B % 32 || (long)m * B > 16384 || keys->s_max / B > 8192) return HISA_ERR_SHAPE;
+  ScoreArgs a = base_args(queries, keys);
+  a.block_idx = nullptr;
+  a.m = m;
+  a.B = B;
+  a.t_begin = 0;
+  a.t_count = queries->T;
+  hipStream_t s = (hipStream_t)stream;
+  // few queries (decode): 8 waves per query shorten the one workgroup a query has; many queries:
+  // 4 waves and two workgroups per CU, as in the Stage 2 kernel
+  const bool wide = queries->T < 256;
+  if (keys->k_dtype == HISA_BF16)
+    st = wide ? launch_indexer<DT_BF16, 8>(a, pooled, k, block_idx, topk_idx, topk_scores, s)
+              : launch_indexer<DT_BF16, 4>(a, pooled, k, block_idx, topk_idx, topk_scores, s);
+  else
+    st = wide ? launch_indexer<DT_FP8, 8>(a, pooled, k, block_idx, topk_idx, topk_scores, s)
+              : launch_indexer<DT_FP8, 4>(a, pooled, k, block_idx, topk_idx, topk_scores, s);
   if (st) return st;
   return launch_status();
 }

@@ -1065,14 +1065,26 @@ __global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(Sel
 // blocks into LDS and selects the top k there; only the k indices leave the CU.  E = candidates
 // per thread in the select (NW * 64 * E >= m * B).  LDS: the per-wave tile rings, then the m*B
 // scores; the select's scratch reuses the ring once scoring is over.
-template <int HG, int KDT, int NW, int NB, int E>
+//
+// E1 > 0: the whole of Algorithm 1 in this one launch.  Stage 1 (Eqs. 5-6) runs first in the
+// same workgroup: the pooled keys (bf16, [n_seq, s_max / B, d]) of the visible blocks go through
+// the same pipeline with the query fragment already in registers, the block scores land in the
+// score area, select_topk keeps m of them (first and own block forced, E1 blocks per thread),
+// and the kept ids stay in LDS for Stage 2 (and are written to block_idx_out if given).
+// sc_floats: size of the score area (>= m * B, and >= NW * 64 * E1 when E1 > 0).
+template <int HG, int KDT, int NW, int NB, int E, int E1 = 0>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(ScoreArgs a, int k,
                                                                            int32_t* topk_idx,
-                                                                           float* topk_scores) {
+                                                                           float* topk_scores,
+                                                                           const void* pooled = nullptr,
+                                                                           int32_t* block_idx_out = nullptr,
+                                                                           int sc_floats = 0) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int NT = NW * 64;
-  constexpr size_t kStageBytes = (size_t)NW * NB * TileGeom<KDT>::kBufBytes;
+  constexpr int kTileBytes = (E1 > 0 && TileGeom<KDT>::kBufBytes < 8192) ? 8192 : TileGeom<KDT>::kBufBytes;
+  constexpr size_t kStageBytes = (size_t)NW * NB * kTileBytes;
   static_assert(sizeof(SelectSmem<NT, E>) <= kStageBytes, "select scratch must fit the rings");
+  static_assert(E1 == 0 || sizeof(SelectSmem<NT, E1 ? E1 : 4>) <= kStageBytes, "select scratch must fit the rings");
   float* sc = reinterpret_cast<float*>(smem + kStageBytes);   // m*B scores (swizzled: score_slot)
   SelectSmem<NT, E>& sm = *reinterpret_cast<SelectSmem<NT, E>*>(smem);
   const int t = a.t_begin + (gridDim.x - 1 - blockIdx.x);
@@ -1084,11 +1096,50 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
   QFrag<HG> f;
   load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
 
-  // Only the slots up to the last kept block are walked (a short prefix keeps few blocks).
-  // Tile v = sub-tile v % tpb of slot v / tpb; wave w takes tiles w, w + NW, ...
   const int tpb = a.B >> 5;
   const int n_blocks = (int)(a.rows_per_seq / a.B);
   const int32_t* blk_ids = a.block_idx + (long)t * a.m;
+  if constexpr (E1 > 0) {
+    // ---- Stage 1: scores of the visible blocks 0 .. b_t, tiles of 32 pooled keys
+    int32_t* blk_lds = reinterpret_cast<int32_t*>(sc + sc_floats);
+    blk_ids = blk_lds;
+    const int n_bvis = pos < 0 ? 0 : pos / a.B + 1;
+    const int nt1 = (n_bvis + 31) >> 5;
+    const int nj1 = nt1 > wave ? (nt1 - wave + NW - 1) / NW : 0;
+    qfrag_ready<HG>(f);
+    const __amdgpu_buffer_rsrc_t prsrc =
+        key_buffer((const char*)pooled + (long)seq * n_blocks * kD * 2, (long)n_blocks * kD * 2);
+    wave_pipeline<HG, DT_BF16, NB>(
+        f, prsrc, prsrc, lds_address(smem) + wave * NB * kTileBytes, nj1,
+        [&](int j) { return (wave + NW * j) * 32; },
+        [&](int j, float s) {
+          const int b = (wave + NW * j) * 32 + (lane & 31);
+          if (lane < 32) sc[b] = b < n_bvis ? s : neg_inf();
+        });
+    __syncthreads();   // block scores complete, rings dead
+    {
+      SelectSmem<NT, E1 ? E1 : 4>& sm1 = *reinterpret_cast<SelectSmem<NT, E1 ? E1 : 4>*>(smem);
+      const int n_last = n_bvis - 1;
+      auto key_of = [&](int i, float v) -> uint32_t {
+        return (i == 0 || i == n_last) ? 0xffffffffu : ordered_key(v);   // first and own block forced
+      };
+      auto load4 = [&](int q) -> uint4 {
+        const float4 v = *reinterpret_cast<const float4*>(sc + 4 * q);
+        return make_uint4(key_of(4 * q, v.x), key_of(4 * q + 1, v.y), key_of(4 * q + 2, v.z),
+                          key_of(4 * q + 3, v.w));
+      };
+      auto load1 = [&](int i) -> uint32_t { return key_of(i, sc[i]); };
+      auto emit = [&](int p, int i, uint32_t) { blk_lds[p] = i; };
+      const int n_kept = select_topk<NT, E1 ? E1 : 4>(sm1, n_bvis, a.m, load4, load1, emit);
+      for (int p = n_kept + threadIdx.x; p < a.m; p += NT) blk_lds[p] = -1;
+    }
+    __syncthreads();   // kept ids visible; the score area and the rings are free again
+    if (block_idx_out)
+      for (int p = threadIdx.x; p < a.m; p += NT) block_idx_out[(long)t * a.m + p] = blk_lds[p];
+  }
+
+  // Only the slots up to the last kept block are walked (a short prefix keeps few blocks).
+  // Tile v = sub-tile v % tpb of slot v / tpb; wave w takes tiles w, w + NW, ...
   int n_used = 0;
   for (int i = lane; i < a.m; i += 64) {
     const int blk = blk_ids[i];
@@ -1125,7 +1176,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
     if (row >= (r < 0 ? 0 : n_vis)) s = neg_inf();
     if (lane < 32) sc[score_slot((wave + NW * j) * 32 + lane)] = s;
   };
-  const uint32_t ring_addr = lds_address(smem) + wave * NB * TileGeom<KDT>::kBufBytes;
+  const uint32_t ring_addr = lds_address(smem) + wave * NB * kTileBytes;
   wave_pipeline<HG, KDT, NB>(f, krsrc, srsrc, ring_addr, nj, row_at, finish);
   __syncthreads();   // scores complete, rings dead: the select scratch may overwrite them
   const int n_cand_slots = n_active * 32;   // score slots actually written

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libh
 
 EXPORTS = ["hisa_pool_blocks", "hisa_pool_append", "hisa_block_score_topk", "hisa_token_refine_topk",
            "hisa_block_sparse_tokens", "hisa_index_iou", "dsa_flat_indexer_topk", "hisa_workspace_bytes",
-           "hisa_status_string", "hisa_version", "hisa_probe_copy", "hisa_probe_mfma"]
+           "hisa_status_string", "hisa_version", "hisa_probe_copy", "hisa_probe_mfma", "hisa_indexer_topk"]
 
 
 class HisaError(RuntimeError):
@@ -71,6 +71,9 @@ def lib() -> C.CDLL:
         L.hisa_workspace_bytes.argtypes = [C.c_int, C.POINTER(_Queries), C.POINTER(_Keys), i32, i32,
                                            i32, i32]
         L.hisa_workspace_bytes.restype = sz
+        L.hisa_indexer_topk.argtypes = [C.POINTER(_Queries), C.POINTER(_Keys), vp, i32, i32, i32, i32, vp, vp,
+                                        vp, vp]
+        L.hisa_indexer_topk.restype = C.c_int
         L.hisa_probe_copy.argtypes = [vp, vp, sz, vp]
         L.hisa_probe_copy.restype = C.c_int
         L.hisa_probe_mfma.argtypes = [vp, i32, C.POINTER(C.c_double), vp]
@@ -279,6 +282,26 @@ def dsa_flat_indexer_topk(queries: Queries, keys: Keys, k: int, topk_idx: Option
                                      _ptr(ws), 0 if ws is None else ws.numel(), _stream(stream))
     _check(st, "dsa_flat_indexer_topk")
     return topk_idx, topk_scores
+
+
+def hisa_indexer_topk(queries: Queries, keys: Keys, pooled: torch.Tensor, pooled_dtype: int, B: int, m: int,
+                      k: int, block_idx: Optional[torch.Tensor] = None, want_block_idx: bool = False,
+                      topk_idx: Optional[torch.Tensor] = None, topk_scores: Optional[torch.Tensor] = None,
+                      want_topk_scores: bool = False, stream=None):
+    """Algorithm 1 in one launch.  Returns (block_idx or None, topk_idx, topk_scores or None)."""
+    dev = queries.q.device
+    T = queries.T
+    if want_block_idx and block_idx is None:
+        block_idx = torch.empty((T, m), dtype=torch.int32, device=dev)
+    if topk_idx is None:
+        topk_idx = torch.empty((T, k), dtype=torch.int32, device=dev)
+    if want_topk_scores and topk_scores is None:
+        topk_scores = torch.empty((T, k), dtype=torch.float32, device=dev)
+    qc, kc = queries.c(), keys.c()
+    st = lib().hisa_indexer_topk(C.byref(qc), C.byref(kc), _ptr(pooled), pooled_dtype, B, m, k, _ptr(block_idx),
+                                 _ptr(topk_idx), _ptr(topk_scores), _stream(stream))
+    _check(st, "hisa_indexer_topk")
+    return block_idx, topk_idx, topk_scores
 
 
 def hisa_probe_copy(src: torch.Tensor, dst: torch.Tensor, stream=None) -> int:

@@ -72,23 +72,7 @@ def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, 
     o_bi, o_J = O.hisa_block_score_topk(**oracle_args(wl, keys=False), pooled=pooled_bits,
                                         pooled_dtype=wl.pooled_dtype, B=wl.B, m=wl.m, queries=qs)
     stats["J_err"] = check_scores(_np(J)[qs], o_J, rtol, "block scores")
-    swaps = 0
-    for i, t in enumerate(qs):
-        b_t = int(pos[t]) // wl.B
-        row = bi[t]
-        v = row[row >= 0]
-        assert v.size == min(wl.m, b_t + 1), (t, v.size)
-        assert v[0] == 0 and v[-1] == b_t, f"query {t}: forced blocks missing"
-        assert np.all(row[v.size:] == -1) and np.all(np.diff(v) > 0)
-        if b_t + 1 > wl.m:
-            # the forced blocks 0 and b_t never take part in a swap: compare the free slots
-            ov = o_bi[i][o_bi[i] >= 0]
-            swaps += check_set(v[1:-1], ov[1:-1], np.arange(1, b_t), o_J[i, 1:b_t], rtol,
-                               f"block set of query {t}")
-        else:
-            assert np.array_equal(v, np.arange(b_t + 1))
-            assert np.all(row[v.size:] == -1)
-    stats["block_swaps"] = swaps
+    stats["block_swaps"] = _check_block_sets(wl, qs, bi, o_bi, o_J, rtol, "two-call")
 
     # ---- Stage 2 (Eqs. 7-9) on the GPU's block_idx: two-kernel path with candidate scores
     topk_idx, topk_sc, cand = hisa.hisa_token_refine_topk(Q, K, wl.B, wl.m, block_idx, wl.k,
@@ -116,6 +100,25 @@ def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, 
         n_idx, _, _ = hisa.hisa_token_refine_topk(Q, K, wl.B, wl.m, block_idx, wl.k)
         torch.cuda.synchronize()
         assert torch.equal(n_idx, topk_idx)
+
+    # ---- Algorithm 1 in one launch (Stage 1 + Stage 2 fused): same rules, its own block_idx
+    single = (wl.q_dtype == "bf16" and wl.pooled_dtype == "bf16" and wl.m * wl.B <= 16384
+              and wl.s_max // wl.B <= 8192 and wl.B % 32 == 0)
+    if single:
+        a_bi, a_ti, a_ts = hisa.hisa_indexer_topk(Q, K, pooled_gpu, pd_code, wl.B, wl.m, wl.k,
+                                                  want_block_idx=True, want_topk_scores=True)
+        _, a_ti2, _ = hisa.hisa_indexer_topk(Q, K, pooled_gpu, pd_code, wl.B, wl.m, wl.k)
+        torch.cuda.synchronize()
+        assert torch.equal(a_ti, a_ti2)
+        abi = _np(a_bi)
+        stats["single_block_swaps"] = _check_block_sets(wl, qs, abi, o_bi, o_J, rtol, "single-launch")
+        if np.array_equal(abi[qs], bi[qs]):
+            s_ti, s_cand = o_ti, o_cand
+        else:   # a legal Stage 1 swap: Stage 2 is judged on the block ids this launch kept
+            s_ti, _, s_cand = O.hisa_token_refine_topk(**oracle_args(wl), B=wl.B, m=wl.m, block_idx=abi[qs],
+                                                       k=wl.k, queries=qs)
+        stats["single_token_swaps"] = _check_token_sets(wl, qs, abi, _np(a_ti), _np(a_ts), s_ti, s_cand, rtol,
+                                                        "single-launch")
 
     # ---- end to end: where the GPU's block set equals the oracle's own, the token set follows it
     o_full = O.hisa_indexer(**oracle_args(wl), seq_len=wl.seq_len, B=wl.B, m=wl.m, k=wl.k,
@@ -146,6 +149,28 @@ def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, 
     if verbose:
         print(wl.name, stats, flush=True)
     return stats
+
+
+def _check_block_sets(wl, qs, bi, o_bi, o_J, rtol, what):
+    """Eq. 6 with the forced blocks: shape rules, then the threshold rule on the free slots."""
+    pos = wl.positions()
+    swaps = 0
+    for i, t in enumerate(qs):
+        b_t = int(pos[t]) // wl.B
+        row = bi[t]
+        v = row[row >= 0]
+        assert v.size == min(wl.m, b_t + 1), (what, t, v.size)
+        assert v[0] == 0 and v[-1] == b_t, f"{what}: query {t}: forced blocks missing"
+        assert np.all(row[v.size:] == -1) and np.all(np.diff(v) > 0)
+        if b_t + 1 > wl.m:
+            # the forced blocks 0 and b_t never take part in a swap: compare the free slots
+            ov = o_bi[i][o_bi[i] >= 0]
+            swaps += check_set(v[1:-1], ov[1:-1], np.arange(1, b_t), o_J[i, 1:b_t], rtol,
+                               f"{what} block set of query {t}")
+        else:
+            assert np.array_equal(v, np.arange(b_t + 1))
+            assert np.all(row[v.size:] == -1)
+    return swaps
 
 
 def _check_token_sets(wl, qs, bi, ti, ts, o_ti, o_cand, rtol, what):
