@@ -546,7 +546,9 @@ __device__ __forceinline__ void find_digit(const uint32_t* hist, uint32_t* bcast
 // list -- many equal keys -- the passes keep running over the registers.)  Positions come from
 // one workgroup scan of per-thread counts: output is ascending, ties go to the lower index.
 // Every thread of the workgroup must call it (it contains workgroup barriers).
-template <int THREADS, int E, class Load4, class Load1, class Emit>
+// SAFE: load4(q) may be called for any q < THREADS * E / 4 (it returns anything beyond n); the
+// loads of a thread are then issued back to back instead of one per guarded branch.
+template <int THREADS, int E, bool SAFE = false, class Load4, class Load1, class Emit>
 __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, int k, Load4 load4,
                                            Load1 load1, Emit emit) {
   static_assert(E % 4 == 0, "elements per thread come in groups of four");
@@ -560,10 +562,19 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
   typedef uint32_t keyvec __attribute__((ext_vector_type(E)));
   keyvec key;   // one vector value, not an array (arrays that live across barriers go to scratch)
   uint32_t cnt = 0, k_and = 0xffffffffu, k_or = 0u;
+  uint4 q4s[E / 4];
 #pragma unroll
   for (int g = 0; g < E / 4; ++g) {
-    uint4 q4 = make_uint4(0u, 0u, 0u, 0u);
-    if (i0 + 4 * g < n) q4 = load4((i0 >> 2) + g);
+    if (SAFE) {
+      q4s[g] = load4((i0 >> 2) + g);
+    } else {
+      q4s[g] = make_uint4(0u, 0u, 0u, 0u);
+      if (i0 + 4 * g < n) q4s[g] = load4((i0 >> 2) + g);
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < E / 4; ++g) {
+    const uint4 q4 = q4s[g];
     const uint32_t kk[4] = {q4.x, q4.y, q4.z, q4.w};
 #pragma unroll
     for (int x = 0; x < 4; ++x) {

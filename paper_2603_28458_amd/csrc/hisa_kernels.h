@@ -643,6 +643,11 @@ struct SelectArgs {
 template <int THREADS, int E, int MAP>
 __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
   __shared__ SelectSmem<THREADS, E> sm;
+  // Rows of up to 8192 entries are also kept in LDS as keys: the later radix passes re-read single
+  // entries, and from global memory every such round costs a full memory latency (it is what a
+  // decode step, with one workgroup per query, mostly waited for).
+  constexpr bool kStaged = THREADS * E * 4 <= 32768;
+  __shared__ __align__(16) uint32_t staged[kStaged ? THREADS * E : 4];
   const int row = blockIdx.y, seg = blockIdx.x;
   const int t = a.t_begin + row;
   const float* sc = a.scores + (long)row * a.ld;
@@ -664,27 +669,36 @@ __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
   float* os = a.out_scores ? a.out_scores + orow * a.k : nullptr;
   const int n_last = n - 1;
   const float* rowp = sc + base;
-  const bool vec_ok = (reinterpret_cast<uintptr_t>(rowp) & 15) == 0;
+  // the row through a buffer descriptor of exactly n floats: no branch at the ragged end
+  const __amdgpu_buffer_rsrc_t rrow = key_buffer(rowp, (long)n * 4);
   auto key_of = [&](int i, float v) -> uint32_t {
     if (MAP == MAP_BLOCKS && (i == 0 || i == n_last)) return 0xffffffffu;   // forced blocks
     return ordered_key(v);
   };
   auto load4 = [&](int q) -> uint4 {
     const int i = 4 * q;
-    float v[4];
-    if (vec_ok && i + 3 < n) {
-      const float4 f = *reinterpret_cast<const float4*>(rowp + i);
-      v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
-    } else {
+    const u32x4v r = __builtin_amdgcn_raw_buffer_load_b128(rrow, i * 4, 0, 0);
+    uint32_t kk[4];
 #pragma unroll
-      for (int x = 0; x < 4; ++x) v[x] = (i + x < n) ? rowp[i + x] : neg_inf();
-    }
-    return make_uint4(key_of(i, v[0]), key_of(i + 1, v[1]), key_of(i + 2, v[2]), key_of(i + 3, v[3]));
+    for (int x = 0; x < 4; ++x) kk[x] = (i + x < n) ? key_of(i + x, __uint_as_float(r[x])) : 0u;
+    const uint4 keys = make_uint4(kk[0], kk[1], kk[2], kk[3]);
+    if (kStaged) *reinterpret_cast<uint4*>(&staged[i]) = keys;   // read back only after a barrier
+    return keys;
   };
-  auto load1 = [&](int i) -> uint32_t { return key_of(i, rowp[i]); };
+  auto load1 = [&](int i) -> uint32_t { return kStaged ? staged[i] : key_of(i, rowp[i]); };
+  // MAP_CAND: a thread's E consecutive candidates lie in one kept block when E divides B; its
+  // token base is then fetched once, not per emitted candidate
+  const bool one_slot = MAP == MAP_CAND && a.B % E == 0;
+  int my_base = 0;
+  if (one_slot) {
+    const int my_slot = (int)(threadIdx.x * E) / a.B;
+    if (my_slot < a.m) my_base = (a.block_idx[(long)t * a.m + my_slot] - my_slot) * a.B;
+  }
   auto emit = [&](int p, int i, uint32_t key) {
     int id;
-    if (MAP == MAP_CAND) {
+    if (MAP == MAP_CAND && one_slot) {
+      id = my_base + i;
+    } else if (MAP == MAP_CAND) {
       const int slot = i / a.B;
       id = a.block_idx[(long)t * a.m + slot] * a.B + (i - slot * a.B);
     } else if (MAP == MAP_PAIRS) {
@@ -695,7 +709,7 @@ __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
     oi[p] = id;
     if (os) os[p] = key_to_score(key);
   };
-  const int n_out = select_topk<THREADS, E>(sm, n, a.k, load4, load1, emit);
+  const int n_out = select_topk<THREADS, E, true>(sm, n, a.k, load4, load1, emit);
   for (int p = n_out + threadIdx.x; p < a.k; p += THREADS) {
     oi[p] = -1;
     if (os) os[p] = neg_inf();
