@@ -89,6 +89,32 @@ def test_validation_of_the_auxiliary_entry_points(lib):
     assert lib.hisa_index_iou(fake, fake, 0, 4, fake, None) == 2
 
 
+def test_validation_of_the_single_launch_call_and_the_probes(lib):
+    fake = 0x1000
+    q, k = _structs()
+    bf16 = hisa.HISA_BF16
+    # hisa_indexer_topk(queries, keys, pooled, pooled_dtype, B, m, k, block_idx, topk_idx, topk_scores, stream)
+    assert lib.hisa_indexer_topk(C.byref(q), C.byref(k), None, bf16, 128, 8, 512, None, fake, None, None) == 1
+    assert lib.hisa_indexer_topk(C.byref(q), C.byref(k), fake, bf16, 128, 8, 512, None, None, None, None) == 1
+    assert lib.hisa_indexer_topk(C.byref(q), C.byref(k), fake + 4, bf16, 128, 8, 512, None, fake, None, None) == 6
+    assert lib.hisa_indexer_topk(C.byref(q), C.byref(k), fake, bf16, 128, 1, 64, None, fake, None, None) == 4    # m < 2
+    assert lib.hisa_indexer_topk(C.byref(q), C.byref(k), fake, bf16, 128, 4, 2048, None, fake, None, None) == 4  # m*B < k
+    assert lib.hisa_indexer_topk(C.byref(q), C.byref(k), fake, hisa.HISA_F32, 128, 8, 512, None, fake, None, None) == 3
+    assert lib.hisa_indexer_topk(C.byref(q), C.byref(k), fake, bf16, 48, 16, 512, None, fake, None, None) == 2   # s_max % B
+    q2, k2 = _structs(s_max=1 << 20)
+    assert lib.hisa_indexer_topk(C.byref(q2), C.byref(k2), fake, bf16, 64, 128, 512, None, fake, None, None) == 2  # > 8192 blocks
+    assert lib.hisa_indexer_topk(C.byref(q2), C.byref(k2), fake, bf16, 256, 128, 512, None, fake, None, None) == 2  # m*B > 16384
+    q3, k3 = _structs(qd=hisa.HISA_F32, kd=hisa.HISA_F32, H=4, d=64)
+    assert lib.hisa_indexer_topk(C.byref(q3), C.byref(k3), fake, hisa.HISA_F32, 128, 8, 512, None, fake, None, None) == 3
+    # probes
+    flop = C.c_double(0.0)
+    assert lib.hisa_probe_copy(None, fake, 1024, None) == 1
+    assert lib.hisa_probe_copy(fake, fake, 1000, None) == 2
+    assert lib.hisa_probe_copy(fake + 8, fake, 1024, None) == 6
+    assert lib.hisa_probe_mfma(None, 10, C.byref(flop), None) == 1
+    assert lib.hisa_probe_mfma(fake, 0, C.byref(flop), None) == 2
+
+
 def test_workspace_sizes(lib):
     q, k = _structs(T=65536, s_max=65536)
     assert lib.hisa_workspace_bytes(hisa.OP_POOL, C.byref(q), C.byref(k), 128, 64, 2048, 0) == 0
