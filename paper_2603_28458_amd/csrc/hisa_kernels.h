@@ -16,7 +16,9 @@ namespace hisa {
 // MFMA-over-epilogue overlap inside a wave is worth more than a third wave.  Deeper rings do not
 // help, neither do LDS reads requested half a tile early, a branch-free step with one DMA
 // instruction per MFMA pair, a raised wave priority over the MFMAs, or touching the lines of the
-// tiles two ahead (all within 2 % or slower): with bf16 keys a tile is 8 KB through the CU's
+// tiles two ahead (all within 2 % or slower), or a fixed grid of workgroups that each walk several
+// queries (10.6 ms with 512 workgroups: the hardware's dynamic placement of one short workgroup
+// per query balances better): with bf16 keys a tile is 8 KB through the CU's
 // vector-memory path per 16 MFMAs, and that path (about 44 B/clk/CU measured, keys L2-resident)
 // saturates together with the matrix cores; with fp8 keys the widening puts the step just past
 // the rate at which vector instructions still issue under the MFMAs.
