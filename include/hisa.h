@@ -30,7 +30,8 @@
  *     (MFMA path, fp32 accumulation; fp8 keys are widened to bf16 exactly and the per-token scale
  *     multiplies the finished score, which equals Eq. 1 on the dequantised key because the scale
  *     is positive).
- *   - top-k / candidate limits: k <= 8192, m <= 1024, m * B <= 65536.
+ *   - top-k / candidate limits: k <= 8192, m <= 1024, m * B <= 65536; one sequence's key array
+ *     (s_max * d elements) must stay below 2 GiB.
  */
 #ifndef HISA_H_
 #define HISA_H_

@@ -48,6 +48,9 @@ int check_keys(const hisa_keys* k, bool need_data) {
   if (!k || !k->seq_len) return HISA_ERR_NULL;
   if (k->n_seq < 1 || k->s_max < 1 || k->d < 1) return HISA_ERR_SHAPE;
   if (k->k_dtype < HISA_F32 || k->k_dtype > HISA_FP8_E4M3) return HISA_ERR_DTYPE;
+  // one sequence's key array is addressed with 32-bit byte offsets (buffer descriptors)
+  const long elem = k->k_dtype == HISA_F32 ? 4 : (k->k_dtype == HISA_BF16 ? 2 : 1);
+  if ((long)k->s_max * k->d * elem >= (1L << 31)) return HISA_ERR_SHAPE;
   if (need_data) {
     if (!k->k) return HISA_ERR_NULL;
     if (k->k_dtype == HISA_FP8_E4M3 && !k->k_scale) return HISA_ERR_NULL;
@@ -324,6 +327,7 @@ int hisa_block_sparse_tokens(const hisa_queries* queries, const hisa_keys* keys,
   a.seq_len = keys->seq_len;
   a.n_seq = keys->n_seq;
   a.rows_per_seq = keys->s_max;
+  a.pos_div = 1;
   a.block_idx = block_idx;
   a.m = m;
   a.B = B;

@@ -55,7 +55,11 @@ __device__ __forceinline__ int query_pos(const ScoreArgs& a, int t, int& seq) {
   s = s < 0 ? 0 : (s >= a.n_seq ? a.n_seq - 1 : s);
   seq = s;
   int pos = a.q_pos ? a.q_pos[t] : a.q_pos0 + t;
-  const int sl = a.seq_len[s];
+  // a sequence cannot be longer than the padded row count of its key array (a bad seq_len must
+  // not turn into an index past the arrays)
+  const long cap = a.rows_per_seq * a.pos_div;
+  int sl = a.seq_len[s];
+  sl = sl < cap ? sl : (int)cap;
   return pos < sl ? pos : sl - 1;
 }
 
@@ -664,7 +668,8 @@ __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
     int pos = a.q_pos ? a.q_pos[t] : a.q_pos0 + t;
     const int sl = a.seq_len[s];
     pos = pos < sl ? pos : sl - 1;
-    const int n_vis = pos < 0 ? 0 : pos / a.pos_div + 1;
+    int n_vis = pos < 0 ? 0 : pos / a.pos_div + 1;
+    n_vis = n_vis < a.ld ? n_vis : (int)a.ld;   // never past the score row, whatever seq_len says
     base = seg * a.seg_len;
     n = n_vis - base;
     n = n < 0 ? 0 : (n > a.seg_len ? a.seg_len : n);
@@ -767,7 +772,8 @@ __global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(Sel
   int pos = a.q_pos ? a.q_pos[t] : a.q_pos0 + t;
   const int sl = a.seq_len[sq];
   pos = pos < sl ? pos : sl - 1;
-  const int n = pos < 0 ? 0 : pos + 1;
+  int n = pos < 0 ? 0 : pos + 1;
+  n = n < a.ld ? n : (int)a.ld;   // never past the score row, whatever seq_len says
   const int k = a.k;
   const float* rowp = a.scores + (long)row * a.ld;
   int32_t* oi = a.out_idx + (long)row * k;

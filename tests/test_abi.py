@@ -60,6 +60,9 @@ def test_host_side_validation_rejects_before_launch(lib):
     q2, k2 = _structs(d=64)
     assert lib.dsa_flat_indexer_topk(C.byref(q2), C.byref(k2), 64, fake, None, fake, 1 << 30, None) == 2
     assert lib.hisa_token_refine_topk(C.byref(q), C.byref(k), 48, 16, fake, 512, fake, None, None, None, 0, None) == 2
+    # a sequence's key array must stay below 2 GiB (32-bit byte offsets)
+    q2, k2 = _structs(s_max=1 << 23)
+    assert lib.dsa_flat_indexer_topk(C.byref(q2), C.byref(k2), 64, fake, None, fake, 1 << 30, None) == 2
     # dtype combinations
     q2, k2 = _structs(qd=hisa.HISA_F32, kd=hisa.HISA_BF16)
     assert lib.dsa_flat_indexer_topk(C.byref(q2), C.byref(k2), 64, fake, None, fake, 1 << 30, None) == 3

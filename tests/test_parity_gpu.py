@@ -195,3 +195,49 @@ def test_block_sparse_tokens_and_iou_diagnostic():
         assert np.all(row[want.size:] == -1), t
         assert abs(iou_h[t] - O.iou(ti_h[t], fi_h[t])) < 1e-6, t
     assert torch.all(hisa.hisa_index_iou(ti, ti) == 1.0)
+
+
+def test_bad_device_side_metadata_stays_in_bounds():
+    # seq_len, q_pos and block_idx live on the device and cannot be validated by the host: the
+    # kernels clamp them.  Whatever they hold, every call must finish and every index it writes
+    # must be -1 or a position inside the padded key array.
+    from paper_2603_28458_amd import hisa
+    wl = W.make_workload("bad_meta", seq_len=2000, T=600, H=64, d=128, B=128, m=4, k=256, q_dtype="bf16",
+                         k_dtype="bf16", seed=150)
+    print(f"\n[parity] {wl.name}", flush=True)
+    Q, K = hisa.to_device(wl)
+    s_max, M = K.s_max, K.s_max // wl.B
+    dev = Q.q.device
+
+    def run_all(Qx, Kx, bi_in=None):
+        pooled = hisa.hisa_pool_blocks(Kx, wl.B)
+        bi, _ = hisa.hisa_block_score_topk(Qx, Kx, pooled, hisa.HISA_BF16, wl.B, wl.m)
+        use = bi if bi_in is None else bi_in
+        outs = [bi]
+        outs.append(hisa.hisa_token_refine_topk(Qx, Kx, wl.B, wl.m, use, wl.k)[0])                      # fused
+        outs.append(hisa.hisa_token_refine_topk(Qx, Kx, wl.B, wl.m, use, wl.k, want_cand_scores=True)[0])  # two kernels
+        outs.append(hisa.hisa_block_sparse_tokens(Qx, Kx, wl.B, wl.m, use))
+        outs.append(hisa.dsa_flat_indexer_topk(Qx, Kx, wl.k)[0])
+        a_bi, a_ti, _ = hisa.hisa_indexer_topk(Qx, Kx, pooled, hisa.HISA_BF16, wl.B, wl.m, wl.k, want_block_idx=True)
+        outs += [a_bi, a_ti]
+        torch.cuda.synchronize()
+        for j, o in enumerate(outs):
+            o = o.cpu().numpy()
+            hi = M if j in (0, 5) else s_max
+            assert ((o == -1) | ((o >= 0) & (o < hi))).all(), f"output {j} out of range"
+
+    # 1. sequence length far beyond the padded array
+    K1 = hisa.Keys(K.k, torch.tensor([s_max + 5000], dtype=torch.int32, device=dev), K.dtype)
+    run_all(Q, K1)
+    # 2. positions below zero and far beyond the sequence
+    pos = torch.arange(600, dtype=torch.int32, device=dev) + 1400
+    pos[::3] = -7
+    pos[1::3] = 10 ** 9
+    Q2 = hisa.Queries(Q.q, Q.w, Q.dtype, q_pos=pos)
+    run_all(Q2, K)
+    # 3. block ids that are negative, far too large, or repeated
+    g = torch.Generator(device="cpu").manual_seed(3)
+    bad = torch.randint(-100, 10 ** 6, (600, wl.m), generator=g, dtype=torch.int64).to(torch.int32)
+    bad[:, 0] = 3
+    bad[:, 1] = 3
+    run_all(Q, K, bi_in=bad.to(dev))
