@@ -94,10 +94,13 @@ def encode(x: np.ndarray, dtype: str) -> np.ndarray:
 
 # ----------------------------------------------------------------------------- Eq. 4: pooling
 def pool_blocks(keys: np.ndarray, k_dtype: str, k_scale, seq_len: np.ndarray, B: int,
-                pooled_dtype: str) -> np.ndarray:
+                pooled_dtype: str, mode: str = "mean") -> np.ndarray:
     """Eq. 4 / Algorithm 1 pooling loop.  keys [n_seq, s_max, d] stored bits -> pooled stored bits
     [n_seq, s_max/B, d].  Block b of sequence n holds tokens bB .. min((b+1)B, seq_len[n]) - 1;
-    blocks with no token are written as zeros."""
+    blocks with no token are written as zeros.  mode "mean" is the paper's method; "max" is the
+    per-dimension maximum the paper names as a possible other Pool (Section 4.1 writes Pool
+    generically; its closing discussion lists max-pooling as future work)."""
+    assert mode in ("mean", "max")
     n_seq, s_max, d = keys.shape
     assert s_max % B == 0
     M = s_max // B
@@ -108,7 +111,7 @@ def pool_blocks(keys: np.ndarray, k_dtype: str, k_scale, seq_len: np.ndarray, B:
             lo, hi = b * B, min((b + 1) * B, L)
             sc = None if k_scale is None else k_scale[n, lo:hi]
             kb = decode(keys[n, lo:hi], k_dtype, sc)
-            out[n, b] = kb.sum(axis=0) / float(hi - lo)
+            out[n, b] = kb.sum(axis=0) / float(hi - lo) if mode == "mean" else kb.max(axis=0)
     return encode(out, pooled_dtype)
 
 

@@ -67,6 +67,32 @@ def test_pooled_keys_are_block_means(k_dtype):
         np.testing.assert_allclose(pooled[0, b].astype(np.float64), want, rtol=1e-6, atol=1e-7)
 
 
+def test_max_pool_variant_pins():
+    # per-dimension maximum: identical keys give that key; never below the mean; a one-token block is
+    # the token; equals a pure-Python maximum; fp8 keys are compared after dequantisation
+    keys = np.zeros((1, 64, 4), dtype=np.float32)
+    keys[0] = [1.5, -2.25, 0.0, 7.0]
+    assert np.array_equal(O.pool_blocks(keys, "f32", None, np.array([64]), 16, "f32", mode="max")[0],
+                          np.tile([1.5, -2.25, 0.0, 7.0], (4, 1)).astype(np.float32))
+    rng = np.random.default_rng(17)
+    keys = rng.standard_normal((2, 48, 8)).astype(np.float32)
+    lens = np.array([48, 33])
+    mx = O.pool_blocks(keys, "f32", None, lens, 16, "f32", mode="max")
+    mean = O.pool_blocks(keys, "f32", None, lens, 16, "f32", mode="mean")
+    assert np.all(mx[0] >= mean[0]) and np.all(mx[1, :3] >= mean[1, :3])
+    assert np.array_equal(mx[1, 2], keys[1, 32])                     # one token present in block 2
+    for n in range(2):
+        for b in range(-(-int(lens[n]) // 16)):
+            for i in range(8):
+                want = max(float(keys[n, s, i]) for s in range(16 * b, min(16 * b + 16, int(lens[n]))))
+                assert mx[n, b, i] == np.float32(want)
+    wl = W.make_workload("mx8", seq_len=64, T=64, H=2, d=16, B=16, m=2, k=16, q_dtype="bf16", k_dtype="fp8_e4m3",
+                         pooled_dtype="f32", seed=18)
+    deq = O.decode(wl.keys, "fp8_e4m3", wl.k_scale)[0]
+    got = O.pool_blocks(wl.keys, "fp8_e4m3", wl.k_scale, wl.seq_len, 16, "f32", mode="max")[0]
+    assert np.array_equal(got, deq.reshape(4, 16, 16).max(axis=1).astype(np.float32))
+
+
 def test_pool_of_identical_keys_is_that_key_and_empty_blocks_are_zero():
     keys = np.zeros((2, 64, 4), dtype=np.float32)
     keys[0, :, :] = [1.5, -2.25, 0.0, 7.0]
