@@ -99,6 +99,15 @@ int hisa_pool_blocks(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_
                      void* pooled, int32_t pooled_dtype, void* stream);
 
 /*
+ * The same call with the per-dimension MAXIMUM over the tokens present in a block instead of their
+ * mean: Eq. 4 is written for a generic Pool, the paper uses the mean and names max-pooling as a
+ * variant to explore.  Everything else as hisa_pool_blocks (a block with no token is zeros); the
+ * later stages take either pooled array.  hisa_pool_append maintains the mean only.
+ */
+int hisa_pool_blocks_max(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_t blk_end,
+                         void* pooled, int32_t pooled_dtype, void* stream);
+
+/*
  * Stage 1 (Eqs. 5-6; Algorithm 1, block-level coarse filter).  For each query, scores the pooled
  * keys of the visible blocks 0 .. b_t (b_t = q_pos / B) and keeps min(m, b_t + 1) blocks: block 0
  * and block b_t always (Section 4.1: first and last block forced, counted inside the budget m),

@@ -256,8 +256,8 @@ const char* hisa_status_string(int status) {
 
 const char* hisa_version(void) { return "0.1"; }
 
-int hisa_pool_blocks(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_t blk_end,
-                     void* pooled, int32_t pooled_dtype, void* stream) {
+static int pool_blocks_impl(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_t blk_end,
+                            void* pooled, int32_t pooled_dtype, bool max_pool, void* stream) {
   int st = check_keys(keys, true);
   if (st) return st;
   if (!pooled) return HISA_ERR_NULL;
@@ -274,8 +274,14 @@ int hisa_pool_blocks(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_
   hipStream_t s = (hipStream_t)stream;
   dim3 grid(blk_end - blk_begin, keys->n_seq);
 #define POOL(KD, PD)                                                                             \
-  hipLaunchKernelGGL((k_pool<KD, PD>), grid, dim3(256), 0, s, keys->k, keys->k_scale,            \
-                     keys->seq_len, (long)keys->s_max, d, B, blk_begin, pooled)
+  do {                                                                                           \
+    if (max_pool)                                                                                \
+      hipLaunchKernelGGL((k_pool<KD, PD, true>), grid, dim3(256), 0, s, keys->k, keys->k_scale,  \
+                         keys->seq_len, (long)keys->s_max, d, B, blk_begin, pooled);             \
+    else                                                                                         \
+      hipLaunchKernelGGL((k_pool<KD, PD, false>), grid, dim3(256), 0, s, keys->k, keys->k_scale, \
+                         keys->seq_len, (long)keys->s_max, d, B, blk_begin, pooled);             \
+  } while (0)
   if (kd == HISA_F32) POOL(DT_F32, DT_F32);
   else if (kd == HISA_BF16 && pooled_dtype == HISA_BF16) POOL(DT_BF16, DT_BF16);
   else if (kd == HISA_BF16) POOL(DT_BF16, DT_F32);
@@ -283,6 +289,16 @@ int hisa_pool_blocks(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_
   else POOL(DT_FP8, DT_F32);
 #undef POOL
   return launch_status();
+}
+
+int hisa_pool_blocks(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_t blk_end,
+                     void* pooled, int32_t pooled_dtype, void* stream) {
+  return pool_blocks_impl(keys, B, blk_begin, blk_end, pooled, pooled_dtype, false, stream);
+}
+
+int hisa_pool_blocks_max(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_t blk_end,
+                         void* pooled, int32_t pooled_dtype, void* stream) {
+  return pool_blocks_impl(keys, B, blk_begin, blk_end, pooled, pooled_dtype, true, stream);
 }
 
 int hisa_pool_append(const hisa_keys* keys, int32_t B, const int32_t* prev_len, int32_t max_new_tokens,

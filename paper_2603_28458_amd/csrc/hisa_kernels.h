@@ -71,7 +71,8 @@ __device__ __forceinline__ int visible_rows(const ScoreArgs& a, int pos) {
 // Eq. 4: block mean pooling.  One workgroup per (block, sequence).  VEC = elements per 16-byte
 // load (4 fp32 / 8 bf16 / 16 fp8).  Thread (rl, col) sums rows rl, rl+RP, ... of its 16-byte
 // column in fp32; the RP partial rows are then reduced through LDS and divided by the count.
-template <int KDT, int PDT>
+// MAXP: per-dimension maximum instead of the mean (the other Pool of Section 4.1's generic Eq. 4).
+template <int KDT, int PDT, bool MAXP = false>
 __device__ __forceinline__ void pool_one_block(const void* __restrict__ keys,
                                                const float* __restrict__ k_scale, int sl, long s_max,
                                                int d, int B, int seq, int b, void* __restrict__ pooled,
@@ -87,22 +88,34 @@ __device__ __forceinline__ void pool_one_block(const void* __restrict__ keys,
   if (nb < 0) nb = 0;
   float acc[VEC];
 #pragma unroll
-  for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+  for (int e = 0; e < VEC; ++e) acc[e] = MAXP ? neg_inf() : 0.f;
+  auto add = [&](float& a, float v) { a = MAXP ? fmaxf(a, v) : a + v; };
   if (rl < RP) {
     const char* base = (const char*)keys + ((long)seq * s_max + lo) * d * (16 / VEC);
     for (int r = rl; r < nb; r += RP) {
       const uint4 v = *reinterpret_cast<const uint4*>(base + ((long)r * VC + col) * 16);
       if (KDT == DT_F32) {
-        acc[0] += __uint_as_float(v.x);
-        acc[1] += __uint_as_float(v.y);
-        acc[2] += __uint_as_float(v.z);
-        acc[3] += __uint_as_float(v.w);
+        add(acc[0], __uint_as_float(v.x));
+        add(acc[1], __uint_as_float(v.y));
+        add(acc[2], __uint_as_float(v.z));
+        add(acc[3], __uint_as_float(v.w));
       } else if (KDT == DT_BF16) {
         const uint32_t ww[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          acc[2 * e] += __uint_as_float(ww[e] << 16);
-          acc[2 * e + 1] += __uint_as_float(ww[e] & 0xffff0000u);
+          add(acc[2 * e], __uint_as_float(ww[e] << 16));
+          add(acc[2 * e + 1], __uint_as_float(ww[e] & 0xffff0000u));
+        }
+      } else if (MAXP) {
+        const float sc = k_scale[(long)seq * s_max + lo + r];
+        const uint32_t ww[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint2 h = fp8x4_to_bf16x4(ww[e]);
+          add(acc[4 * e + 0], sc * __uint_as_float(h.x << 16));
+          add(acc[4 * e + 1], sc * __uint_as_float(h.x & 0xffff0000u));
+          add(acc[4 * e + 2], sc * __uint_as_float(h.y << 16));
+          add(acc[4 * e + 3], sc * __uint_as_float(h.y & 0xffff0000u));
         }
       } else {
         const float sc = k_scale[(long)seq * s_max + lo + r];
@@ -122,9 +135,9 @@ __device__ __forceinline__ void pool_one_block(const void* __restrict__ keys,
   }
   __syncthreads();
   for (int i = tid; i < d; i += 256) {
-    float s = 0.f;
-    for (int r = 0; r < RP; ++r) s += part[r * d + i];
-    const float mean = nb > 0 ? s / (float)nb : 0.f;
+    float s = MAXP ? neg_inf() : 0.f;
+    for (int r = 0; r < RP; ++r) add(s, part[r * d + i]);
+    const float mean = nb > 0 ? (MAXP ? s : s / (float)nb) : 0.f;
     const long o = ((long)seq * M + b) * d + i;
     if (PDT == DT_F32)
       ((float*)pooled)[o] = mean;
@@ -133,7 +146,7 @@ __device__ __forceinline__ void pool_one_block(const void* __restrict__ keys,
   }
 }
 
-template <int KDT, int PDT>
+template <int KDT, int PDT, bool MAXP = false>
 __global__ __launch_bounds__(256) void k_pool(const void* __restrict__ keys,
                                               const float* __restrict__ k_scale,
                                               const int32_t* __restrict__ seq_len, long s_max, int d,
@@ -141,8 +154,8 @@ __global__ __launch_bounds__(256) void k_pool(const void* __restrict__ keys,
   constexpr int VEC = KDT == DT_F32 ? 4 : (KDT == DT_BF16 ? 8 : 16);
   __shared__ float part[256 * VEC];
   const int seq = blockIdx.y;
-  pool_one_block<KDT, PDT>(keys, k_scale, seq_len[seq], s_max, d, B, seq, blk_begin + blockIdx.x,
-                           pooled, part);
+  pool_one_block<KDT, PDT, MAXP>(keys, k_scale, seq_len[seq], s_max, d, B, seq, blk_begin + blockIdx.x,
+                                 pooled, part);
 }
 
 // Incremental pooled-cache update (Section 4.1): workgroup (j, n) re-pools block prev_len[n]/B + j

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libh
 
 EXPORTS = ["hisa_pool_blocks", "hisa_pool_append", "hisa_block_score_topk", "hisa_token_refine_topk",
            "hisa_block_sparse_tokens", "hisa_index_iou", "dsa_flat_indexer_topk", "hisa_workspace_bytes",
-           "hisa_status_string", "hisa_version", "hisa_probe_copy", "hisa_probe_mfma", "hisa_indexer_topk"]
+           "hisa_status_string", "hisa_version", "hisa_probe_copy", "hisa_probe_mfma", "hisa_indexer_topk", "hisa_pool_blocks_max"]
 
 
 class HisaError(RuntimeError):
@@ -53,6 +53,8 @@ def lib() -> C.CDLL:
         vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
         L.hisa_pool_blocks.argtypes = [C.POINTER(_Keys), i32, i32, i32, vp, i32, vp]
         L.hisa_pool_blocks.restype = C.c_int
+        L.hisa_pool_blocks_max.argtypes = [C.POINTER(_Keys), i32, i32, i32, vp, i32, vp]
+        L.hisa_pool_blocks_max.restype = C.c_int
         L.hisa_pool_append.argtypes = [C.POINTER(_Keys), i32, vp, i32, vp, i32, vp]
         L.hisa_pool_append.restype = C.c_int
         L.hisa_block_sparse_tokens.argtypes = [C.POINTER(_Queries), C.POINTER(_Keys), i32, i32, vp, vp, vp]
@@ -174,17 +176,24 @@ _POOLED_TORCH = {HISA_F32: torch.float32, HISA_BF16: torch.bfloat16}
 
 def hisa_pool_blocks(keys: Keys, B: int, pooled: Optional[torch.Tensor] = None,
                      pooled_dtype: int = HISA_BF16, blk_begin: int = 0, blk_end: Optional[int] = None,
-                     stream=None) -> torch.Tensor:
-    """Eq. 4: pooled [n_seq, s_max / B, d]."""
+                     stream=None, max_pool: bool = False) -> torch.Tensor:
+    """Eq. 4: pooled [n_seq, s_max / B, d] (max_pool: hisa_pool_blocks_max, the maximum instead of the mean)."""
     M = keys.s_max // B
     if pooled is None:
         pooled = torch.zeros((keys.n_seq, M, keys.d), dtype=_POOLED_TORCH[pooled_dtype],
                              device=keys.k.device)
     kc = keys.c()
-    st = lib().hisa_pool_blocks(C.byref(kc), B, blk_begin, M if blk_end is None else blk_end,
-                                _ptr(pooled), pooled_dtype, _stream(stream))
-    _check(st, "hisa_pool_blocks")
+    fn = lib().hisa_pool_blocks_max if max_pool else lib().hisa_pool_blocks
+    st = fn(C.byref(kc), B, blk_begin, M if blk_end is None else blk_end, _ptr(pooled), pooled_dtype,
+            _stream(stream))
+    _check(st, "hisa_pool_blocks_max" if max_pool else "hisa_pool_blocks")
     return pooled
+
+
+def hisa_pool_blocks_max(keys: Keys, B: int, pooled: Optional[torch.Tensor] = None, pooled_dtype: int = HISA_BF16,
+                         blk_begin: int = 0, blk_end: Optional[int] = None, stream=None) -> torch.Tensor:
+    """Eq. 4 with Pool = per-dimension maximum."""
+    return hisa_pool_blocks(keys, B, pooled, pooled_dtype, blk_begin, blk_end, stream, max_pool=True)
 
 
 def hisa_pool_append(keys: Keys, B: int, prev_len: torch.Tensor, max_new_tokens: int, pooled: torch.Tensor,

@@ -241,3 +241,34 @@ def test_bad_device_side_metadata_stays_in_bounds():
     bad[:, 0] = 3
     bad[:, 1] = 3
     run_all(Q, K, bi_in=bad.to(dev))
+
+
+@pytest.mark.parametrize("k_dtype,pooled_dtype", [("bf16", "bf16"), ("fp8_e4m3", "bf16"), ("f32", "f32")])
+def test_max_pool_variant(k_dtype, pooled_dtype):
+    # Eq. 4 with Pool = per-dimension maximum, ragged last block, several sequences; then Stage 1 on
+    # the max-pooled keys against the oracle's Stage 1 on the same pooled bits
+    from oracle import hisa_oracle as O
+    from paper_2603_28458_amd import hisa
+    from tests.util import check_scores, oracle_args, rtol_for
+    f32 = k_dtype == "f32"
+    wl = W.make_workload(f"maxpool_{k_dtype}", n_seq=3, seq_len=[1000, 517, 64], T=3, H=4 if f32 else 64,
+                         d=64 if f32 else 128, B=64, m=4, k=64, q_dtype="f32" if f32 else "bf16", k_dtype=k_dtype,
+                         pooled_dtype=pooled_dtype, mode="decode", seed=160)
+    print(f"\n[parity] {wl.name}", flush=True)
+    Q, K = hisa.to_device(wl)
+    pd = hisa.DTYPE_CODE[pooled_dtype]
+    got = hisa.hisa_pool_blocks_max(K, wl.B, pooled_dtype=pd)
+    torch.cuda.synchronize()
+    bits = got.view(torch.int16).cpu().numpy().view(np.uint16) if pooled_dtype == "bf16" else got.cpu().numpy()
+    want = O.pool_blocks(wl.keys, wl.k_dtype, wl.k_scale, wl.seq_len, wl.B, pooled_dtype, mode="max")
+    g = O.decode(bits, pooled_dtype).reshape(-1, wl.d)
+    w_ = O.decode(want, pooled_dtype).reshape(-1, wl.d)
+    if k_dtype == "fp8_e4m3":
+        check_scores(g, w_, rtol_for(wl), "max-pooled keys")      # scale * code rounds once more in fp32
+    else:
+        assert np.array_equal(bits, want), "a maximum of stored values is exact"
+    bi, J = hisa.hisa_block_score_topk(Q, K, got, pd, wl.B, wl.m, want_scores=True)
+    torch.cuda.synchronize()
+    o_bi, o_J = O.hisa_block_score_topk(**oracle_args(wl, keys=False), pooled=bits, pooled_dtype=pooled_dtype,
+                                        B=wl.B, m=wl.m, queries=np.arange(wl.T))
+    check_scores(J.cpu().numpy(), o_J, rtol_for(wl), "block scores on max-pooled keys")
