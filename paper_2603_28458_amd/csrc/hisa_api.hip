@@ -165,7 +165,9 @@ SelectArgs select_base(const hisa_queries* q, const hisa_keys* k) {
 template <int HG, int KDT, int EC>
 int launch_fused_hg(const ScoreArgs& a, int k, int32_t* topk_idx, float* topk_scores,
                     hipStream_t st) {
-  constexpr int NW = kFusedWaves;
+  // more than 8192 candidates: their scores (64 KB) leave room for one workgroup per CU only, so
+  // that one gets 8 waves (two per SIMD; and 32 instead of 64 candidates per thread in the select)
+  constexpr int NW = EC > 32 ? 8 : kFusedWaves;
   constexpr int E = ((EC * 4 + NW - 1) / NW + 3) / 4 * 4;
   const size_t sh = (size_t)NW * kNBuf * TileGeom<KDT>::kBufBytes + (size_t)a.m * a.B * 4;
   auto kern = k_refine_fused<HG, KDT, NW, kNBuf, E>;

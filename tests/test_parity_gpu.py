@@ -44,6 +44,14 @@ def test_ablation_block_shapes_at_fixed_candidate_budget(B, m):
     _run(wl, queries=sample_queries(wl, 48))
 
 
+@pytest.mark.parametrize("k_dtype", ["bf16", "fp8_e4m3"])
+def test_more_than_8192_candidates(k_dtype):
+    # m*B = 12800 (> 8192): the fused Stage 2 runs 8 waves per query; 320 queries at the end of 20000 keys
+    wl = W.make_workload(f"cand12800_{k_dtype}", seq_len=20000, T=320, H=64, d=128, B=128, m=100, k=2048,
+                         q_dtype="bf16", k_dtype=k_dtype, seed=145)
+    _run(wl, queries=sample_queries(wl, 32))
+
+
 def test_32_heads_and_fp8():
     wl = W.make_workload("H32", seq_len=900, T=900, H=32, d=128, B=128, m=3, k=300, q_dtype="bf16",
                          k_dtype="fp8_e4m3", seed=103)
