@@ -156,8 +156,11 @@ def _check_block_sets(wl, qs, bi, o_bi, o_J, rtol, what):
     pos = wl.positions()
     swaps = 0
     for i, t in enumerate(qs):
-        b_t = int(pos[t]) // wl.B
         row = bi[t]
+        if pos[t] < 0:                       # a query on an empty sequence sees no block
+            assert np.all(row == -1), (what, t)
+            continue
+        b_t = int(pos[t]) // wl.B
         v = row[row >= 0]
         assert v.size == min(wl.m, b_t + 1), (what, t, v.size)
         assert v[0] == 0 and v[-1] == b_t, f"{what}: query {t}: forced blocks missing"

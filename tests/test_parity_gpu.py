@@ -104,6 +104,13 @@ def test_degenerate_inputs():
     assert st["iou_hisa_flat"] == 1.0
 
 
+def test_empty_sequence_in_a_decode_batch():
+    # a sequence with no key at all: its query sees nothing, every output row is -1 padding
+    wl = W.make_workload("empty_seq", n_seq=3, seq_len=[300, 0, 129], T=3, H=64, d=128, B=128, m=2, k=64,
+                         q_dtype="bf16", k_dtype="bf16", mode="decode", seed=170)
+    _run(wl)
+
+
 def test_ties_and_zero_scores():
     # every dot product negative -> every score exactly 0 -> the lowest indices win everywhere
     wl = W.make_workload("zeros", seq_len=1500, T=1500, H=64, d=128, B=128, m=4, k=300, q_dtype="bf16",
