@@ -38,3 +38,21 @@ def test_config4_decode_32x128k():
 
 def test_config5_chunk_16k_against_1m_fp8():
     _run("chunk16k_1m_fp8", 48, 6)
+
+
+def test_maximum_block_count_budget_and_k():
+    # the limits of the boundary: 65536 pooled keys per query (B = 32 over 2M tokens), m = 1024 kept blocks
+    # (32768 candidates), k = 8192; four queries at the end of the context.  (The flat call at k = 8192 over
+    # 2M keys is outside its own limit -- 32 segments x 8192 -- and is not part of this case.)
+    wl = W.make_workload("max_M_m_k", seq_len=2097152, T=4, H=64, d=128, B=32, m=1024, k=8192, q_dtype="bf16",
+                         k_dtype="bf16", seed=180)
+    print(f"\n[parity-full] {wl.name}: blocks={wl.s_max // wl.B} m={wl.m} k={wl.k}", flush=True)
+    run_and_check(wl, check_flat=False, verbose=True)
+
+
+def test_maximum_candidate_count():
+    # m * B = 65536 candidates per query (the limit), k = 8192, through the two-kernel Stage 2
+    wl = W.make_workload("max_cand", seq_len=131072, T=4, H=64, d=128, B=64, m=1024, k=8192, q_dtype="bf16",
+                         k_dtype="fp8_e4m3", seed=181)
+    print(f"\n[parity-full] {wl.name}: candidates={wl.m * wl.B} k={wl.k}", flush=True)
+    run_and_check(wl, check_flat=False, verbose=True)
