@@ -1,9 +1,9 @@
 // Device-side building blocks of the HISA indexer kernels (gfx950 / CDNA4, wave64).
 //
-//  * QFrag / score_tile: the query-heads x key-tile contraction of Eq. 1 / Eq. 5 of the paper on
-//    the 32x32x16 bf16 MFMA, with the ReLU, gate and head-sum epilogue in registers.
+//  * QFrag / mfma_tile / tile_epilogue: the query-heads x key-tile contraction of Eq. 1 / Eq. 5 of
+//    the paper on the 32x32x16 bf16 MFMA, with the ReLU, gate and head-sum epilogue in registers.
 //  * tile staging: a 32-key x 128-dim key tile in LDS as 512 16-byte chunks, XOR-swizzled so that
-//    both the contiguous store and the MFMA-layout load are bank-conflict free.
+//    both the lane-contiguous global->LDS transfer and the MFMA-layout load are bank-conflict free.
 //  * select_topk: exact per-row top-k (Eqs. 2, 6, 9) by MSB-first radix select on order-preserving
 //    keys held in registers, ties to the lower index, output in ascending index order.
 //  * score_slot: the swizzled LDS position of a candidate's score, conflict-free both for the
@@ -37,15 +37,6 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint4 u) {
   Pack128 p;
   p.u = u;
   return p.v;
-}
-
-// Orders LDS traffic of one wave: what the wave's lanes stored before is visible to what its
-// lanes load after (LDS serves one wave's requests in issue order; this stops the compiler from
-// reordering across the point).
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // ------------------------------------------------------------------------------------------
@@ -99,68 +90,16 @@ __device__ __forceinline__ float relu(float x) {
   return __builtin_bit_cast(float, b > 0 ? b : 0);
 }
 
-// Score of the 32 keys of a staged tile against every head of the query:
-// sum_j w_j * max(0, q_j . k).  Every lane returns the score of key (lane % 32).
-template <int HG>
-__device__ __forceinline__ float score_tile(const QFrag<HG>& f, const uint4* tile) {
-  const int lane = lane_id();
-  const int half = lane >> 5;
-  const int r = lane & 31;
-  f32x16 acc[HG];
-#pragma unroll
-  for (int g = 0; g < HG; ++g)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[g][i] = 0.f;
-#pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
-    const int c = 2 * kk + half;
-    const bf16x8 kv = as_bf16x8(tile[r * 16 + (c ^ (r & 15))]);
-#pragma unroll
-    for (int g = 0; g < HG; ++g)
-      acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[g][kk], kv, acc[g], 0, 0, 0);
-  }
-  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-#pragma unroll
-  for (int g = 0; g < HG; ++g) {
-#pragma unroll
-    for (int i = 0; i < 16; i += 4) {
-      s0 = __builtin_fmaf(relu(acc[g][i + 0]), f.w[g][i + 0], s0);
-      s1 = __builtin_fmaf(relu(acc[g][i + 1]), f.w[g][i + 1], s1);
-      s2 = __builtin_fmaf(relu(acc[g][i + 2]), f.w[g][i + 2], s2);
-      s3 = __builtin_fmaf(relu(acc[g][i + 3]), f.w[g][i + 3], s3);
-    }
-  }
-  float s = (s0 + s1) + (s2 + s3);
-  s += __shfl_xor(s, 32);
-  return s;
-}
-
 // The same contraction and epilogue as two separate steps, so that a kernel can overlap the
 // epilogue of one tile with the MFMAs of the next (software pipelining inside one wave).
 template <int HG>
 using accvec = float __attribute__((ext_vector_type(16 * HG)));
 typedef uint32_t u32x32 __attribute__((ext_vector_type(32)));
 
-// B operands of one staged tile: 8 chunks per lane, chunk kk = contraction step kk.
-__device__ __forceinline__ u32x32 lds_read_tile(const uint4* tile) {
-  const int lane = lane_id();
-  const int half = lane >> 5;
-  const int r = lane & 31;
-  u32x32 kv;
-#pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
-    const uint4 x = tile[r * 16 + ((2 * kk + half) ^ (r & 15))];
-    kv[4 * kk + 0] = x.x;
-    kv[4 * kk + 1] = x.y;
-    kv[4 * kk + 2] = x.z;
-    kv[4 * kk + 3] = x.w;
-  }
-  return kv;
-}
-
-// The same reads issued as raw instructions, for a ring of several tiles per wave: for a plain LDS load the compiler first waits for
-// EVERY pending global->LDS transfer of the wave, which would undo the look-ahead of the tile
-// ring.  The caller waits for the tile's DMA before calling; the data is complete on return.
+// B operands of one staged tile: 8 chunks per lane, chunk kk = contraction step kk.  The reads
+// are raw instructions: for a plain LDS load the compiler first waits for EVERY pending
+// global->LDS transfer of the wave, which would undo the look-ahead of the tile ring.  The caller
+// waits for the tile's DMA before calling; the data is complete on return.
 typedef uint32_t u32x4e __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ u32x32 lds_read_tile_raw(uint32_t tile_addr) {
@@ -250,41 +189,8 @@ __device__ __forceinline__ float tile_epilogue(const QFrag<HG>& f, const accvec<
 // A staging step moves chunk position p = i*64 + lane, so consecutive lanes write consecutive
 // 16-byte LDS words and read one 256-byte key row per 16 lanes.
 
-// The chunks a lane holds between fetch and store are kept in ONE vector value (not an array):
-// arrays that live across a barrier end up in scratch memory.
-typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
-
-template <class V>
-__device__ __forceinline__ void put4(V& v, int i, uint4 x) {
-  v[4 * i + 0] = x.x;
-  v[4 * i + 1] = x.y;
-  v[4 * i + 2] = x.z;
-  v[4 * i + 3] = x.w;
-}
-
-template <class V>
-__device__ __forceinline__ uint4 get4(const V& v, int i) {
-  return make_uint4(v[4 * i + 0], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]);
-}
-
-// 2-byte (bf16) keys: 8 chunks per lane per tile.
-__device__ __forceinline__ u32x32 tile_fetch_bf16(const uint16_t* __restrict__ base, long row0,
-                                                  long n_rows) {
-  const int lane = lane_id();
-  u32x32 v;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int p = i * 64 + lane;
-    const int r = p >> 4, c = p & 15;
-    long gr = row0 + r;
-    gr = gr < n_rows ? gr : n_rows - 1;
-    put4(v, i, *reinterpret_cast<const uint4*>(base + gr * kD + ((c ^ (r & 15)) << 3)));
-  }
-  return v;
-}
-
-// The same fetch for a tile that lies wholly inside the key array: a wave-uniform tile base plus
-// eight per-lane byte offsets that do not depend on the tile (computed once per kernel).
+// A tile's global address = a wave-uniform tile base plus eight per-lane byte offsets that do not
+// depend on the tile (computed once per kernel).
 typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ u32x8 tile_lane_offsets_bf16() {
@@ -307,26 +213,6 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t key_buffer(const void* base, l
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
 }
 
-__device__ __forceinline__ u32x32 tile_fetch_bf16(__amdgpu_buffer_rsrc_t rsrc, int tile_byte_off,
-                                                  const u32x8& o) {
-  u32x32 v;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const u32x4v x = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)o[i], tile_byte_off, 0);
-    v[4 * i + 0] = x[0];
-    v[4 * i + 1] = x[1];
-    v[4 * i + 2] = x[2];
-    v[4 * i + 3] = x[3];
-  }
-  return v;
-}
-
-__device__ __forceinline__ void tile_store_bf16(uint4* tile, const u32x32& v) {
-  const int lane = lane_id();
-#pragma unroll
-  for (int i = 0; i < 8; ++i) tile[i * 64 + lane] = get4(v, i);
-}
-
 // Exact widening of 4 e4m3fn codes (one dword) to 4 bf16 (every e4m3 value is a bf16 value).
 __device__ __forceinline__ uint2 fp8x4_to_bf16x4(uint32_t word) {
   union {
@@ -338,23 +224,7 @@ __device__ __forceinline__ uint2 fp8x4_to_bf16x4(uint32_t word) {
   return make_uint2(lo.u, hi.u);
 }
 
-// 1-byte (fp8) keys: 4 fetches of 16 codes per lane per tile, widened on the way into LDS.
-__device__ __forceinline__ u32x16 tile_fetch_fp8(const uint8_t* __restrict__ base, long row0,
-                                                 long n_rows) {
-  const int lane = lane_id();
-  u32x16 v;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int p = i * 64 + lane;
-    const int r = p >> 3, c8 = p & 7;
-    long gr = row0 + r;
-    gr = gr < n_rows ? gr : n_rows - 1;
-    put4(v, i, *reinterpret_cast<const uint4*>(base + gr * kD + (c8 << 4)));
-  }
-  return v;
-}
-
-// The same tile moved global -> LDS directly (no registers): lane l of step i deposits its 16
+// A tile moves global -> LDS directly (no registers): lane l of step i deposits its 16
 // bytes at LDS byte address lds_addr + (i*64 + l)*16, which is the staged layout above.
 typedef __attribute__((address_space(3))) void lds_void;
 
@@ -435,38 +305,6 @@ __device__ __forceinline__ float lds_read_f32_raw(uint32_t addr) {
 template <int N>
 __device__ __forceinline__ void wait_vmem_le() {
   __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
-}
-
-// Wait until every outstanding global load (vmcnt) / LDS access (lgkmcnt) of this wave is done.
-__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0f70); }
-__device__ __forceinline__ void wait_lds() { __builtin_amdgcn_s_waitcnt(0xc07f); }
-
-// Whole-tile fetch of fp8 keys: the 4 KB of a tile are contiguous and taken in lane order.
-__device__ __forceinline__ u32x16 tile_fetch_fp8(__amdgpu_buffer_rsrc_t rsrc, int tile_byte_off) {
-  const int o = lane_id() << 4;
-  u32x16 v;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const u32x4v x = __builtin_amdgcn_raw_buffer_load_b128(rsrc, o + i * 1024, tile_byte_off, 0);
-    v[4 * i + 0] = x[0];
-    v[4 * i + 1] = x[1];
-    v[4 * i + 2] = x[2];
-    v[4 * i + 3] = x[3];
-  }
-  return v;
-}
-
-__device__ __forceinline__ void tile_store_fp8(uint4* tile, const u32x16& v) {
-  const int lane = lane_id();
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int p = i * 64 + lane;
-    const int r = p >> 3, c8 = p & 7;
-    const uint2 a = fp8x4_to_bf16x4(v[4 * i + 0]), b = fp8x4_to_bf16x4(v[4 * i + 1]);
-    const uint2 c = fp8x4_to_bf16x4(v[4 * i + 2]), d = fp8x4_to_bf16x4(v[4 * i + 3]);
-    tile[r * 16 + ((2 * c8) ^ (r & 15))] = make_uint4(a.x, a.y, b.x, b.y);
-    tile[r * 16 + ((2 * c8 + 1) ^ (r & 15))] = make_uint4(c.x, c.y, d.x, d.y);
-  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -721,10 +559,6 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
   const uint32_t b = __float_as_uint(x);
   return (uint16_t)((b + 0x7fffu + ((b >> 16) & 1u)) >> 16);
-}
-
-__device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) {
-  return __uint_as_float(((uint32_t)h) << 16);
 }
 
 }  // namespace hisa

@@ -311,41 +311,6 @@ __global__ __launch_bounds__(256) void k_score_ranges_f32(ScoreArgs a, int keys_
   }
 }
 
-// ------------------------------------------------------------------------------------------
-// One staged tile: fetch (global -> registers), store (registers -> LDS, widening fp8).
-template <int KDT>
-struct TileRegs {
-  typedef typename std::conditional<KDT == DT_BF16, u32x32, u32x16>::type vec_t;
-  vec_t v;
-};
-
-template <int KDT>
-__device__ __forceinline__ void tile_fetch(TileRegs<KDT>& r, const void* base, long row0,
-                                           long n_rows) {
-  if constexpr (KDT == DT_BF16)
-    r.v = tile_fetch_bf16((const uint16_t*)base, row0, n_rows);
-  else
-    r.v = tile_fetch_fp8((const uint8_t*)base, row0, n_rows);
-}
-
-// Fetch through the sequence's buffer descriptor (tile_byte_off is wave-uniform).
-template <int KDT>
-__device__ __forceinline__ void tile_fetch_buf(TileRegs<KDT>& r, __amdgpu_buffer_rsrc_t rsrc,
-                                               int tile_byte_off, const u32x8& lane_offs) {
-  if constexpr (KDT == DT_BF16)
-    r.v = tile_fetch_bf16(rsrc, tile_byte_off, lane_offs);
-  else
-    r.v = tile_fetch_fp8(rsrc, tile_byte_off);
-}
-
-template <int KDT>
-__device__ __forceinline__ void tile_store(uint4* tile, const TileRegs<KDT>& r) {
-  if constexpr (KDT == DT_BF16)
-    tile_store_bf16(tile, r.v);
-  else
-    tile_store_fp8(tile, r.v);
-}
-
 // Where virtual tile v of a query lives: key rows [row0, row0+32), output slots [out0, out0+32).
 // Flat / Stage 1: tile v covers rows 32v ..; gather (Stage 2): tile v is sub-tile v % (B/32) of
 // the kept block in slot v / (B/32).  row0 < 0: the slot is empty (-1 padding).
