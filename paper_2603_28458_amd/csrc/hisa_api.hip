@@ -113,6 +113,19 @@ void launch_score(int path, int key_dt, ScoreArgs a, long n_rows_max, bool conse
     return;
   }
   const bool gather = a.block_idx != nullptr;
+  if (!gather && consecutive && a.t_count >= 2048 && key_dt == HISA_BF16 && a.rows_per_seq <= 512) {
+    // all rows fit in LDS (Stage 1 up to 512 blocks): resident tiles, 64 queries per workgroup
+    constexpr int NQ = 8;
+    const size_t sh = (size_t)((a.rows_per_seq + 31) / 32) * 8192;
+    dim3 grid((a.t_count + 8 * NQ - 1) / (8 * NQ));
+    auto launch = [&](auto kern) {
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
+      hipLaunchKernelGGL(kern, grid, dim3(512), sh, st, a);
+    };
+    if (a.H == 64) launch(k_score_resident<2, NQ>);
+    else launch(k_score_resident<1, NQ>);
+    return;
+  }
   if (!gather && consecutive && a.t_count >= 64) {
     if (key_dt == HISA_BF16) launch_prefill_mfma<DT_BF16>(a, st);
     else launch_prefill_mfma<DT_FP8>(a, st);

@@ -606,6 +606,68 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Eq. 5 / Eq. 1 on MFMA for a causal prefill of ONE sequence whose rows (pooled keys, normally)
+// all fit in LDS: up to 512 bf16 rows = 16 tiles of 32 = 128 KB.  One workgroup of 8 waves stages
+// the rows its queries can see ONCE (cooperative DMA, one barrier) and then every wave walks NQ
+// queries of its own against the resident tiles: no DMA, no barrier and no tile traffic per query;
+// what is left per query is its 16 KB fragment from HBM, and eight waves per CU with one such load
+// in flight each keep that stream busy while the others compute.  Workgroup g serves the 8 * NQ
+// consecutive queries from 8 * NQ * g, wave w the queries w, w + 8, ...; longest prefixes first.
+template <int HG, int NQ>
+__global__ __launch_bounds__(512) void k_score_resident(ScoreArgs a) {
+  extern __shared__ __align__(16) unsigned char tiles[];   // [n_sub][8192]
+  const int g = gridDim.x - 1 - blockIdx.x;
+  const int th = threadIdx.x, lane = th & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(th >> 6);
+  const int t0 = g * 8 * NQ;
+  const int tl_last = (t0 + 8 * NQ - 1) < a.t_count ? (t0 + 8 * NQ - 1) : a.t_count - 1;
+  int seq_last;
+  const int n_max = visible_rows(a, query_pos(a, a.t_begin + tl_last, seq_last));
+  const int n_sub = (n_max + 31) >> 5;
+  __amdgpu_buffer_rsrc_t krsrc, srsrc;
+  key_buffers<DT_BF16>(a, 0, krsrc, srsrc);
+  const uint32_t tiles_addr = lds_address(tiles);
+  {
+    const u32x8 lane_offs = tile_lane_offsets_bf16();
+    for (int u = wave; u < n_sub; u += 8) tile_dma_bf16(krsrc, tiles_addr + u * 8192, u * 32 * (kD * 2), lane_offs);
+    wait_vmem_le<0>();
+  }
+  __syncthreads();
+  for (int i = 0; i < NQ; ++i) {
+    const int tl = t0 + i * 8 + wave;
+    if (tl >= a.t_count) break;          // wave-uniform; no barrier below
+    const int t = a.t_begin + tl;
+    int seq;
+    const int n_vis = visible_rows(a, query_pos(a, t, seq));
+    const int nu = (n_vis + 31) >> 5;    // <= n_sub: positions grow with the query index
+    if (nu <= 0) continue;
+    float* out = a.out + (long)tl * a.ld;
+    QFrag<HG> f;
+    load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
+    qfrag_ready<HG>(f);
+    auto store = [&](int u, float s) {
+      const int row = u * 32 + (lane & 31);
+      if (lane < 32 && row < n_vis) out[row] = s;
+    };
+    // MFMAs of sub-tile u over the epilogue of sub-tile u-1 (two accumulator sets, unrolled by two)
+    accvec<HG> acc_a = mfma_tile<HG>(f, lds_read_tile_raw(tiles_addr)), acc_b;
+    int u = 0;                           // acc_a holds sub-tile u
+    for (; u + 2 < nu; u += 2) {
+      acc_b = mfma_tile<HG>(f, lds_read_tile_raw(tiles_addr + (u + 1) * 8192));
+      store(u, tile_epilogue<HG>(f, acc_a));
+      acc_a = mfma_tile<HG>(f, lds_read_tile_raw(tiles_addr + (u + 2) * 8192));
+      store(u + 1, tile_epilogue<HG>(f, acc_b));
+    }
+    if (u + 1 < nu) {
+      acc_b = mfma_tile<HG>(f, lds_read_tile_raw(tiles_addr + (u + 1) * 8192));
+      store(u, tile_epilogue<HG>(f, acc_a));
+      store(u + 1, tile_epilogue<HG>(f, acc_b));
+    } else {
+      store(u, tile_epilogue<HG>(f, acc_a));
+    }
+  }
+}
+
 // Row-wise exact top-k over scores in global memory (Eqs. 2, 6, 9).
 enum : int { MAP_FLAT = 0, MAP_BLOCKS = 1, MAP_CAND = 2, MAP_PAIRS = 3 };
 
