@@ -119,7 +119,8 @@ void launch_score(int path, int key_dt, ScoreArgs a, long n_rows_max, bool conse
     const size_t sh = (size_t)((a.rows_per_seq + 31) / 32) * 8192;
     dim3 grid((a.t_count + 8 * NQ - 1) / (8 * NQ));
     auto launch = [&](auto kern) {
-      hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
+      // a refusal here makes the launch below fail, which the entry point reports (launch_status)
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
       hipLaunchKernelGGL(kern, grid, dim3(512), sh, st, a);
     };
     if (a.H == 64) launch(k_score_resident<2, NQ>);

@@ -168,8 +168,8 @@ __device__ __forceinline__ float add_halves(float s) {
   return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
 }
 
-template <int HG>
-__device__ __forceinline__ float tile_epilogue(const QFrag<HG>& f, const accvec<HG>& acc) {
+template <int HG, class Frag>
+__device__ __forceinline__ float tile_epilogue(const Frag& f, const accvec<HG>& acc) {
   float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
 #pragma unroll
   for (int g = 0; g < HG; ++g) {
@@ -182,6 +182,109 @@ __device__ __forceinline__ float tile_epilogue(const QFrag<HG>& f, const accvec<
     }
   }
   return add_halves((s0 + s1) + (s2 + s3));
+}
+
+// ------------------------------------------------------------------------------------------
+// fp8 keys: the contraction runs on the fp8 MFMA (v_mfma_f32_32x32x64_f8f6f4, e4m3 x e4m3, twice the
+// bf16 rate) with the key codes as they are stored, and the bf16 query written as a sum of two e4m3
+// numbers.  Per head row the query is first multiplied by a power of two that puts its largest
+// magnitude into [128, 256); hi = e4m3(q), lo = e4m3(q - hi): the 8 significant bits of a bf16
+// value split 4 + 4, so hi + lo == q exactly for every element within 2^-9 of the row's largest,
+// and within 2^-17 of that largest below (the e4m3 subnormal grid).  Two MFMAs (hi, lo) per 64
+// contraction elements accumulate into the same registers; the power of two goes into the gate.
+// Lane l keeps the contraction elements it holds in the bf16 fragment (d = 16*kk + 8*(l/32) + e):
+// MFMA step ks takes kk = 4*ks .. 4*ks+3, and the key operand follows the same order, which an
+// MFMA permits because A and B index the contraction dimension by the same (lane / 32, byte).
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x16 __attribute__((ext_vector_type(16)));
+
+template <int HG>
+struct QFrag8 {
+  i32x8 hi[HG][2], lo[HG][2];
+  float w[HG][16];
+};
+
+template <int HG>
+__device__ __forceinline__ void split_qfrag(const QFrag<HG>& f, QFrag8<HG>& o) {
+  const int half = lane_id() >> 5;
+#pragma unroll
+  for (int g = 0; g < HG; ++g) {
+    // largest bf16 magnitude (sign cleared) of head row g*32 + lane%32: 64 elements here, 64 in lane ^ 32
+    uint32_t mag = 0;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      Pack128 p;
+      p.v = f.a[g][kk];
+      const uint32_t d[4] = {p.u.x, p.u.y, p.u.z, p.u.w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const uint32_t lo16 = d[c] & 0x7fffu, hi16 = (d[c] >> 16) & 0x7fffu;
+        mag = mag > lo16 ? mag : lo16;
+        mag = mag > hi16 ? mag : hi16;
+      }
+    }
+    {
+      const uint32_t other = (uint32_t)__shfl_xor((int)mag, 32);
+      mag = mag > other ? mag : other;
+    }
+    int e = (int)(mag >> 7);                  // biased exponent of the largest magnitude
+    e = e < 8 ? 8 : (e > 254 ? 254 : e);      // (rows below 2^-119 lose their low bits: they score ~0)
+    const float up = __uint_as_float((uint32_t)(261 - e) << 23);     // 2^(134 - e)
+    const float down = __uint_as_float((uint32_t)(e - 7) << 23);     // 2^(e - 134)
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      Pack128 p;
+      p.v = f.a[g][kk];
+      const uint32_t d[4] = {p.u.x, p.u.y, p.u.z, p.u.w};
+      int whi[2] = {0, 0}, wlo[2] = {0, 0};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const float x0 = __uint_as_float(d[c] << 16) * up;
+        const float x1 = __uint_as_float(d[c] & 0xffff0000u) * up;
+        int h = __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, 0, false);
+        const auto back = __builtin_amdgcn_cvt_pk_f32_fp8(h, false);
+        const int l = __builtin_amdgcn_cvt_pk_fp8_f32(x0 - back[0], x1 - back[1], 0, false);
+        whi[c >> 1] |= (h & 0xffff) << (16 * (c & 1));
+        wlo[c >> 1] |= (l & 0xffff) << (16 * (c & 1));
+      }
+      o.hi[g][kk >> 2][2 * (kk & 3) + 0] = whi[0];
+      o.hi[g][kk >> 2][2 * (kk & 3) + 1] = whi[1];
+      o.lo[g][kk >> 2][2 * (kk & 3) + 0] = wlo[0];
+      o.lo[g][kk >> 2][2 * (kk & 3) + 1] = wlo[1];
+    }
+    // the gate of accumulator register i belongs to head row 8*(i/4) + 4*half + i%4, whose
+    // power of two sits in the lane of that number
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      o.w[g][i] = f.w[g][i] * __shfl(down, 8 * (i >> 2) + 4 * half + (i & 3));
+  }
+}
+
+template <int HG>
+__device__ __forceinline__ accvec<HG> mfma_tile(const QFrag8<HG>& f, const u32x16& kv) {
+  f32x16 acc[HG];
+#pragma unroll
+  for (int g = 0; g < HG; ++g)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[g][i] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    i32x8 b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) b[i] = (int)kv[8 * ks + i];
+#pragma unroll
+    for (int g = 0; g < HG; ++g)
+      acc[g] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.hi[g][ks], b, acc[g], 0, 0, 0, 0, 0, 0);
+#pragma unroll
+    for (int g = 0; g < HG; ++g)
+      acc[g] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.lo[g][ks], b, acc[g], 0, 0, 0, 0, 0, 0);
+  }
+  accvec<HG> out;
+#pragma unroll
+  for (int g = 0; g < HG; ++g)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) out[g * 16 + i] = acc[g][i];
+  return out;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -256,10 +359,11 @@ __device__ __forceinline__ void tile_dma_fp8(__amdgpu_buffer_rsrc_t rsrc, __amdg
 }
 
 // B operands of an fp8 tile staged by tile_dma_fp8: eight 8-byte reads per lane (raw
-// instructions, see lds_read_tile_raw), widened exactly to bf16.  The data is complete on return.
+// instructions, see lds_read_tile_raw); read kk brings the codes of d = 16*kk + 8*(lane/32) .. +7
+// of key row lane % 32, the order split_qfrag gives the query operand.  Complete on return.
 typedef uint32_t u32x2e __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ u32x32 lds_read_tile_fp8_raw(uint32_t tile_addr) {
+__device__ __forceinline__ u32x16 lds_read_tile_fp8_raw(uint32_t tile_addr) {
   const int lane = lane_id();
   const int half = lane >> 5;
   const int r = lane & 31;
@@ -282,14 +386,11 @@ __device__ __forceinline__ u32x32 lds_read_tile_fp8_raw(uint32_t tile_addr) {
       : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3]), "v"(ad[4]), "v"(ad[5]), "v"(ad[6]), "v"(ad[7])
       : "memory");
   const u32x2e xs[8] = {x0, x1, x2, x3, x4, x5, x6, x7};
-  u32x32 kv;
+  u32x16 kv;
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) {
-    const uint2 lo = fp8x4_to_bf16x4(xs[kk][0]), hi = fp8x4_to_bf16x4(xs[kk][1]);
-    kv[4 * kk + 0] = lo.x;
-    kv[4 * kk + 1] = lo.y;
-    kv[4 * kk + 2] = hi.x;
-    kv[4 * kk + 3] = hi.y;
+    kv[2 * kk + 0] = xs[kk][0];
+    kv[2 * kk + 1] = xs[kk][1];
   }
   return kv;
 }
@@ -339,17 +440,18 @@ struct SelectSmem {
   static constexpr int NW = THREADS / 64;
   static constexpr int CAP = 2048;   // entries of the threshold-bin list (fast path)
   uint32_t hist[256];
-  uint32_t red[4 * NW];
+  uint32_t red[5 * NW];
   uint32_t bcast[4];
   uint32_t n_list;
   uint16_t list[CAP];
 };
 
-// Finds, in a 256-bin histogram of digit counts, the digit that holds the krem-th largest
-// element: counts above it < krem <= counts above it + its own.  Wave 0 only; publishes
-// bcast[0] = digit, bcast[1] = krem - (count above), bcast[2] = count in the digit's bin.
-__device__ __forceinline__ void find_digit(const uint32_t* hist, uint32_t* bcast, uint32_t krem,
-                                           int lane) {
+// Finds, in a 256-bin histogram of counts (bin 255 = largest keys), the bin that holds the
+// krem-th largest element: counts above it < krem <= counts above it + its own.  Wave 0 only;
+// publishes bcast[0] = bin, bcast[1] = krem - (count above), bcast[2] = count in that bin.
+// If krem exceeds the histogram's total (the element lies below the binned range):
+// bcast[0] = 0xffffffff, bcast[1] = krem - total, bcast[2] = total.
+__device__ __forceinline__ void find_bin(const uint32_t* hist, uint32_t* bcast, uint32_t krem, int lane) {
   const uint32_t c0 = hist[4 * lane + 0], c1 = hist[4 * lane + 1];
   const uint32_t c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
   const uint32_t s = c0 + c1 + c2 + c3;
@@ -371,6 +473,17 @@ __device__ __forceinline__ void find_digit(const uint32_t* hist, uint32_t* bcast
     bcast[1] = krem - above;
     bcast[2] = mine;
   }
+  if (lane == 0 && krem > S) {
+    bcast[0] = 0xffffffffu;
+    bcast[1] = krem - S;
+    bcast[2] = S;
+  }
+}
+
+// The digit variant used by the streaming select (bins = one radix digit).
+__device__ __forceinline__ void find_digit(const uint32_t* hist, uint32_t* bcast, uint32_t krem,
+                                           int lane) {
+  find_bin(hist, bcast, krem, lane);
 }
 
 // Exact top-k of one row by one workgroup of THREADS threads, n <= THREADS * E elements.
@@ -378,11 +491,18 @@ __device__ __forceinline__ void find_digit(const uint32_t* hist, uint32_t* bcast
 //   Thread t holds the E consecutive elements t*E .. t*E+E-1 in registers.
 //   emit(pos, i, key): element i is the pos-th selected, in ascending i.
 // Returns the number selected: min(k, #candidates).  Order: key descending, then i ascending.
-// Method: MSB-first radix select on the bits below the candidates' common prefix.  The first
-// 8-bit pass histograms the registers; the few elements that fall into the threshold bin are
-// listed in LDS and the remaining passes run over that list only.  (If the bin overflows the
-// list -- many equal keys -- the passes keep running over the registers.)  Positions come from
-// one workgroup scan of per-thread counts: output is ascending, ties go to the lower index.
+// Method: the threshold (the k-th largest key) is bracketed by key RANGES, each pass cutting the
+// current range [lo, hi] into up to 256 equal bins, counting the candidates per bin (LDS atomics)
+// and keeping the bin that holds the k-th.  Scores of one row crowd into one or two binades, so
+// bins over the row's own range spread the counts where radix digits of the float bits would pile
+// them onto a few addresses.  The first range is [largest of the per-thread minima, row maximum]:
+// the low end sits near the row's 15th percentile whatever a few tiny scores do, and if the k-th
+// lies below it the next pass bins [row minimum, that low end).  Keys equal to 0xffffffff (rows
+// forced to the top by a caller) are counted apart and do not stretch the range.  The candidates
+// of the bin kept by the first pass are listed in LDS and later passes run over that list only
+// (if it overflows the list -- many equal keys -- they keep running over the registers); a pass
+// whose bin is taken whole ends the search.  Positions come from one workgroup scan of
+// per-thread counts: output is ascending, ties go to the lower index.
 // Every thread of the workgroup must call it (it contains workgroup barriers).
 // SAFE: load4(q) may be called for any q < THREADS * E / 4 (it returns anything beyond n); the
 // loads of a thread are then issued back to back instead of one per guarded branch.
@@ -392,6 +512,7 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
   static_assert(E % 4 == 0, "elements per thread come in groups of four");
   constexpr int NW = THREADS / 64;
   constexpr int CAP = SelectSmem<THREADS, E>::CAP;
+  constexpr uint32_t TOP = 0xffffffffu;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
@@ -399,7 +520,7 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
 
   typedef uint32_t keyvec __attribute__((ext_vector_type(E)));
   keyvec key;   // one vector value, not an array (arrays that live across barriers go to scratch)
-  uint32_t cnt = 0, k_and = 0xffffffffu, k_or = 0u;
+  uint32_t cnt = 0, n_top = 0, t_min = TOP, t_max = 0u;
   uint4 q4s[E / 4];
 #pragma unroll
   for (int g = 0; g < E / 4; ++g) {
@@ -418,99 +539,115 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
     for (int x = 0; x < 4; ++x) {
       const uint32_t kj = (i0 + 4 * g + x < n) ? kk[x] : 0u;
       key[4 * g + x] = kj;
-      if (kj) {
-        ++cnt;
-        k_and &= kj;
-        k_or |= kj;
-      }
+      cnt += kj != 0u;
+      n_top += kj == TOP;
+      // minimum / maximum over the keys in 1 .. TOP-1: 0 - 1 wraps to TOP and TOP - 1 stays large,
+      // so both ends of the key space drop out of the minimum; TOP + 1 wraps to 0 for the maximum
+      const uint32_t for_min = kj - 1u, for_max = kj + 1u;
+      t_min = for_min < t_min ? for_min : t_min;
+      t_max = for_max > t_max ? for_max : t_max;
     }
   }
+  // t_min = (smallest key in 1..TOP-1) - 1, or >= TOP - 1 if there is none; t_max = (largest such key) + 1, or 0/1
+  uint32_t lo_est = t_min >= TOP - 1u ? 0u : t_min + 1u;   // this thread's minimum, 0 if it has none
+  uint32_t k_min = t_min >= TOP - 1u ? TOP : t_min + 1u;
+  uint32_t k_max = t_max <= 1u ? 0u : t_max - 1u;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
     cnt += __shfl_xor(cnt, off);
-    k_and &= __shfl_xor(k_and, off);
-    k_or |= __shfl_xor(k_or, off);
+    n_top += __shfl_xor(n_top, off);
+    const uint32_t a = __shfl_xor(lo_est, off), b = __shfl_xor(k_min, off), c = __shfl_xor(k_max, off);
+    lo_est = a > lo_est ? a : lo_est;
+    k_min = b < k_min ? b : k_min;
+    k_max = c > k_max ? c : k_max;
   }
   if (lane == 0) {
     sm.red[wave] = cnt;
-    sm.red[NW + wave] = k_and;
-    sm.red[2 * NW + wave] = k_or;
+    sm.red[NW + wave] = n_top;
+    sm.red[2 * NW + wave] = lo_est;
+    sm.red[3 * NW + wave] = k_min;
+    sm.red[4 * NW + wave] = k_max;
   }
   if (tid == 0) sm.n_list = 0u;
-  for (int b = tid; b < 256; b += THREADS) sm.hist[b] = 0u;
   __syncthreads();
   cnt = 0;
-  k_and = 0xffffffffu;
-  k_or = 0u;
+  n_top = 0;
+  lo_est = 0u;
+  k_min = TOP;
+  k_max = 0u;
 #pragma unroll
   for (int v = 0; v < NW; ++v) {
     cnt += sm.red[v];
-    k_and &= sm.red[NW + v];
-    k_or |= sm.red[2 * NW + v];
+    n_top += sm.red[NW + v];
+    const uint32_t a = sm.red[2 * NW + v], b = sm.red[3 * NW + v], c = sm.red[4 * NW + v];
+    lo_est = a > lo_est ? a : lo_est;
+    k_min = b < k_min ? b : k_min;
+    k_max = c > k_max ? c : k_max;
   }
   const int n_valid = (int)cnt;
 
   uint32_t tau = 0u;   // threshold key: everything above is selected
   uint32_t r = 0u;     // how many elements equal to tau are selected (lowest indices first)
-  if (n_valid > k) {
-    const uint32_t diff = k_and ^ k_or;
-    int hi = diff ? 32 - __builtin_clz(diff) : 0;           // low bits that vary among candidates
-    uint32_t pref = (hi >= 32) ? 0u : (k_or >> hi) << hi;   // bits above are common to all
-    uint32_t krem = (uint32_t)k;
+  if (n_valid > k && (uint32_t)k <= n_top) {
+    tau = TOP;
+    r = (uint32_t)k;
+  } else if (n_valid > k) {
+    uint32_t krem = (uint32_t)k - n_top;   // > 0; at least krem + 1 keys lie in [k_min, k_max]
+    uint32_t lo = lo_est, hi = k_max;      // current range; k_min <= lo <= hi <= k_max < TOP
     bool on_list = false;
-    uint32_t n_c = 0;
-    if (hi > 0) {
-      // first pass: every candidate shares the bits above hi, so all of them are counted
-      const int wbits = hi < 8 ? hi : 8;
-      const int shift = hi - wbits;
-      const uint32_t dmask = (1u << wbits) - 1u;
-#pragma unroll
-      for (int j = 0; j < E; ++j)
-        if (key[j]) atomicAdd(&sm.hist[(key[j] >> shift) & dmask], 1u);
-      __syncthreads();
-      if (wave == 0) find_digit(sm.hist, sm.bcast, krem, lane);
-      __syncthreads();
-      const uint32_t D = sm.bcast[0];
-      krem = sm.bcast[1];
-      n_c = sm.bcast[2];
-      pref |= D << shift;
-      hi = shift;
-      if (hi > 0 && n_c <= (uint32_t)CAP) {
-        on_list = true;
-#pragma unroll
-        for (int j = 0; j < E; ++j)
-          if (key[j] && ((key[j] >> shift) & dmask) == D)
-            sm.list[atomicAdd(&sm.n_list, 1u)] = (uint16_t)(i0 + j);
-      }
-    }
-    while (hi > 0) {
-      const int wbits = hi < 8 ? hi : 8;
-      const int shift = hi - wbits;
-      const uint32_t dmask = (1u << wbits) - 1u;
-      __syncthreads();   // list complete / previous digit read by everyone
+    uint32_t n_listed = 0;
+    while (true) {
+      const uint32_t width = hi - lo;
+      const int s = width ? (32 - __builtin_clz(width) > 8 ? 32 - __builtin_clz(width) - 8 : 0) : 0;
+      __syncthreads();   // list complete / previous result read by everyone
       for (int b = tid; b < 256; b += THREADS) sm.hist[b] = 0u;
       __syncthreads();
       if (on_list) {
-        for (uint32_t p = tid; p < n_c; p += THREADS) {
-          const uint32_t kj = load1((int)sm.list[p]);
-          if ((kj >> hi) == (pref >> hi)) atomicAdd(&sm.hist[(kj >> shift) & dmask], 1u);
+        for (uint32_t p = tid; p < n_listed; p += THREADS) {
+          const uint32_t dk = load1((int)sm.list[p]) - lo;   // keys below lo (and 0) wrap far above width
+          if (dk <= width) atomicAdd(&sm.hist[dk >> s], 1u);
         }
       } else {
 #pragma unroll
         for (int j = 0; j < E; ++j) {
-          const uint32_t kj = key[j];
-          if (kj && (kj >> hi) == (pref >> hi)) atomicAdd(&sm.hist[(kj >> shift) & dmask], 1u);
+          const uint32_t dk = key[j] - lo;
+          if (dk <= width) atomicAdd(&sm.hist[dk >> s], 1u);
         }
       }
       __syncthreads();
-      if (wave == 0) find_digit(sm.hist, sm.bcast, krem, lane);
+      if (wave == 0) find_bin(sm.hist, sm.bcast, krem, lane);
       __syncthreads();
-      pref |= sm.bcast[0] << shift;
+      const uint32_t D = sm.bcast[0];
       krem = sm.bcast[1];
-      hi = shift;
+      const uint32_t n_c = sm.bcast[2];
+      if (D == TOP) {
+        // the k-th lies below the range (first pass only: its low end is an estimate)
+        hi = lo - 1u;
+        lo = k_min;
+        continue;
+      }
+      const uint32_t bin_lo = lo + (D << s);
+      if (s == 0) {          // bins are single keys
+        tau = bin_lo;
+        r = krem;
+        break;
+      }
+      if (krem == n_c) {     // the whole bin is selected
+        tau = bin_lo - 1u;
+        r = 0u;
+        break;
+      }
+      const uint32_t span = (1u << s) - 1u;
+      hi = (hi - bin_lo) > span ? bin_lo + span : hi;
+      lo = bin_lo;
+      if (!on_list && n_c <= (uint32_t)CAP) {
+        on_list = true;
+        n_listed = n_c;
+#pragma unroll
+        for (int j = 0; j < E; ++j)
+          if (key[j] - lo <= hi - lo) sm.list[atomicAdd(&sm.n_list, 1u)] = (uint16_t)(i0 + j);
+      }
     }
-    tau = pref;
-    r = krem;
   }
 
   // Positions in index order: thread t's elements precede thread t+1's, so an exclusive scan of

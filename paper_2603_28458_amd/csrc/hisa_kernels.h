@@ -350,8 +350,24 @@ struct TileGeom {
   static constexpr int kBufBytes = KDT == DT_BF16 ? 8192 : 4096 + 256;  // LDS per staged tile
 };
 
+// The query fragment and the key-tile registers a key type computes with: bf16 keys on the bf16
+// MFMA, fp8 keys (as stored) on the fp8 MFMA against the two-term e4m3 form of the query.
+template <int HG, int KDT>
+struct Operands {
+  using Frag = QFrag<HG>;
+  using Tile = u32x32;
+  static __device__ __forceinline__ void make(const QFrag<HG>& f, Frag& o) { o = f; }
+};
+template <int HG>
+struct Operands<HG, DT_FP8> {
+  using Frag = QFrag8<HG>;
+  using Tile = u32x16;
+  static __device__ __forceinline__ void make(const QFrag<HG>& f, Frag& o) { split_qfrag<HG>(f, o); }
+};
+
 template <int HG, int KDT, int NB, class RowAt, class Finish>
-__device__ __forceinline__ void wave_pipeline(const QFrag<HG>& f, __amdgpu_buffer_rsrc_t krsrc,
+__device__ __forceinline__ void wave_pipeline(const typename Operands<HG, KDT>::Frag& f,
+                                              __amdgpu_buffer_rsrc_t krsrc,
                                               __amdgpu_buffer_rsrc_t srsrc, uint32_t ring_addr, int nj,
                                               RowAt row_at, Finish finish) {
   static_assert(NB >= 1 && NB <= 3, "ring of one to three tiles");
@@ -373,7 +389,8 @@ __device__ __forceinline__ void wave_pipeline(const QFrag<HG>& f, __amdgpu_buffe
     else if (later == 1) wait_vmem_le<L>();
     else wait_vmem_le<0>();
   };
-  auto read_tile = [&](int buf, float& scale) -> u32x32 {
+  using Tile = typename Operands<HG, KDT>::Tile;
+  auto read_tile = [&](int buf, float& scale) -> Tile {
     const uint32_t addr = ring_addr + buf * BB;
     if constexpr (KDT == DT_BF16) {
       scale = 1.f;
@@ -392,17 +409,17 @@ __device__ __forceinline__ void wave_pipeline(const QFrag<HG>& f, __amdgpu_buffe
   // one step: tile jn -> acc_out (matrix cores) while tile jn-1 = acc_in is finished (vector ALU)
   auto step = [&](int jn, const accvec<HG>& acc_in, float sc_in, accvec<HG>& acc_out, float& sc_out) {
     wait_tile(jn);
-    const u32x32 kv = read_tile(buf, sc_out);
+    const Tile kv = read_tile(buf, sc_out);
     if (jn + NB < nj) dma(jn + NB, buf);
     buf = (buf + 1 == NB) ? 0 : buf + 1;
-    acc_out = mfma_tile<HG>(f, kv);
+    acc_out = mfma_tile(f, kv);
     finish(jn - 1, tile_epilogue<HG>(f, acc_in) * sc_in);
   };
   wait_tile(0);
-  const u32x32 kv0 = read_tile(0, sc_a);
+  const Tile kv0 = read_tile(0, sc_a);
   if (NB < nj) dma(NB, 0);
   buf = (NB == 1) ? 0 : 1;
-  accvec<HG> acc_a = mfma_tile<HG>(f, kv0), acc_b;
+  accvec<HG> acc_a = mfma_tile(f, kv0), acc_b;
   int j = 0;                         // acc_a holds tile j
   for (; j + 2 < nj; j += 2) {
     step(j + 1, acc_a, sc_a, acc_b, sc_b);
@@ -491,11 +508,13 @@ __global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
     outs.lo = __shfl(my_out, src);
   }
   qfrag_ready<HG>(f);
+  typename Operands<HG, KDT>::Frag fo;
+  Operands<HG, KDT>::make(f, fo);
   __amdgpu_buffer_rsrc_t krsrc, srsrc;
   key_buffers<KDT>(a, seq, krsrc, srsrc);
   const uint32_t ring_addr = lds_address(ring) + wave * NB * TileGeom<KDT>::kBufBytes;
   wave_pipeline<HG, KDT, NB>(
-      f, krsrc, srsrc, ring_addr, nj, [&](int j) { return rows.at(j); },
+      fo, krsrc, srsrc, ring_addr, nj, [&](int j) { return rows.at(j); },
       [&](int j, float s) {
         const int row = rows.at(j) + (lane & 31);
         if (row >= n_vis) s = neg_inf();
@@ -530,8 +549,8 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
   const int n_iter = (n_max + 63) >> 6;
   float* out = a.out + (long)(active ? tl : 0) * a.ld;
 
-  QFrag<HG> f;
-  load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
+  QFrag<HG> fq;
+  load_qfrag<HG>(fq, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
 
   __amdgpu_buffer_rsrc_t krsrc, srsrc;
   key_buffers<KDT>(a, 0, krsrc, srsrc);
@@ -564,7 +583,8 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
                                                  (it * 64 + sub_w * 32) * 4, 0, 0);
     }
   };
-  auto read_sub = [&](int buf, int sub, float& scale) -> u32x32 {
+  using Tile = typename Operands<HG, KDT>::Tile;
+  auto read_sub = [&](int buf, int sub, float& scale) -> Tile {
     const uint32_t addr = tiles_addr + (buf * 2 + sub) * BB;
     if constexpr (KDT == DT_BF16) {
       scale = 1.f;
@@ -581,7 +601,9 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
   };
 
   if (n_iter > 0) dma_tile(0, 0);
-  qfrag_ready<HG>(f);
+  qfrag_ready<HG>(fq);
+  typename Operands<HG, KDT>::Frag f;
+  Operands<HG, KDT>::make(fq, f);
   wait_vmem_le<0>();
   __syncthreads();
   accvec<HG> acc_a, acc_b;
@@ -590,13 +612,13 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
     const int buf = it & 1;
     if (it + 1 < n_iter) dma_tile(it + 1, buf ^ 1);
     {
-      const u32x32 kv = read_sub(buf, 0, sc_b);
-      acc_b = mfma_tile<HG>(f, kv);                                        // sub-tile 2it
+      const Tile kv = read_sub(buf, 0, sc_b);
+      acc_b = mfma_tile(f, kv);                                        // sub-tile 2it
       if (it > 0) finish(2 * it - 1, tile_epilogue<HG>(f, acc_a) * sc_a);  // previous tile's second half
     }
     {
-      const u32x32 kv = read_sub(buf, 1, sc_a);
-      acc_a = mfma_tile<HG>(f, kv);                                        // sub-tile 2it+1
+      const Tile kv = read_sub(buf, 1, sc_a);
+      acc_a = mfma_tile(f, kv);                                        // sub-tile 2it+1
       finish(2 * it, tile_epilogue<HG>(f, acc_b) * sc_b);
     }
     wait_vmem_le<0>();   // the next tile (and this wave's score stores) have landed
@@ -1229,6 +1251,8 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
   rows.lo = row_of(wave + NW * (lane < nj ? lane : 0));
   rows.hi = (nj > 64) ? row_of(wave + NW * (lane + 64 < nj ? lane + 64 : 0)) : -1;
   qfrag_ready<HG>(f);
+  typename Operands<HG, KDT>::Frag fo;
+  Operands<HG, KDT>::make(f, fo);
   __amdgpu_buffer_rsrc_t krsrc, srsrc;
   key_buffers<KDT>(a, seq, krsrc, srsrc);
   auto row_at = [&](int j) {
@@ -1242,7 +1266,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
     if (lane < 32) sc[score_slot((wave + NW * j) * 32 + lane)] = s;
   };
   const uint32_t ring_addr = lds_address(smem) + wave * NB * kTileBytes;
-  wave_pipeline<HG, KDT, NB>(f, krsrc, srsrc, ring_addr, nj, row_at, finish);
+  wave_pipeline<HG, KDT, NB>(fo, krsrc, srsrc, ring_addr, nj, row_at, finish);
   __syncthreads();   // scores complete, rings dead: the select scratch may overwrite them
   const int n_cand_slots = n_active * 32;   // score slots actually written
 
