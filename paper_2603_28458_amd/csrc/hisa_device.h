@@ -224,8 +224,8 @@ __device__ __forceinline__ void split_qfrag(const QFrag<HG>& f, QFrag8<HG>& o) {
       }
     }
     {
-      const uint32_t other = (uint32_t)__shfl_xor((int)mag, 32);
-      mag = mag > other ? mag : other;
+      const auto sw = __builtin_amdgcn_permlane32_swap(mag, mag, false, false);   // both halves of the row
+      mag = sw[0] > sw[1] ? sw[0] : sw[1];
     }
     int e = (int)(mag >> 7);                  // biased exponent of the largest magnitude
     e = e < 8 ? 8 : (e > 254 ? 254 : e);      // (rows below 2^-119 lose their low bits: they score ~0)
@@ -409,6 +409,56 @@ __device__ __forceinline__ void wait_vmem_le() {
 }
 
 // ------------------------------------------------------------------------------------------
+// Wave64 reductions and scans on the DPP / lane-swap paths of the vector ALU (a __shfl goes
+// through the LDS crossbar and costs a memory-latency round trip per step).
+template <int CTRL, int ROW_MASK = 0xf, int BANK_MASK = 0xf>
+__device__ __forceinline__ uint32_t dpp_or0(uint32_t v) {   // lanes without a source read 0
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, BANK_MASK, false);
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_perm(uint32_t v) {  // permutations: every lane has a source
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+}
+
+// op (associative, commutative) over all 64 lanes, result in every lane.
+template <class Op>
+__device__ __forceinline__ uint32_t wave_all(uint32_t v, Op op) {
+  v = op(v, dpp_perm<0xB1>(v));    // quad_perm [1,0,3,2]
+  v = op(v, dpp_perm<0x4E>(v));    // quad_perm [2,3,0,1]
+  v = op(v, dpp_perm<0x141>(v));   // row_half_mirror
+  v = op(v, dpp_perm<0x140>(v));   // row_mirror
+  {
+    const auto sw = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = op((uint32_t)sw[0], (uint32_t)sw[1]);
+  }
+  {
+    const auto sw = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    v = op((uint32_t)sw[0], (uint32_t)sw[1]);
+  }
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+  return wave_all(v, [](uint32_t a, uint32_t b) { return a + b; });
+}
+__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
+  return wave_all(v, [](uint32_t a, uint32_t b) { return a > b ? a : b; });
+}
+__device__ __forceinline__ uint32_t wave_min(uint32_t v) {
+  return wave_all(v, [](uint32_t a, uint32_t b) { return a < b ? a : b; });
+}
+
+// Inclusive prefix sum over the 64 lanes.
+__device__ __forceinline__ uint32_t wave_scan_add(uint32_t v) {
+  v += dpp_or0<0x111>(v);        // row_shr:1
+  v += dpp_or0<0x112>(v);        // row_shr:2
+  v += dpp_or0<0x114>(v);        // row_shr:4
+  v += dpp_or0<0x118>(v);        // row_shr:8
+  v += dpp_or0<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+  v += dpp_or0<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
+// ------------------------------------------------------------------------------------------
 // Order-preserving key of a score: larger score <=> larger key.  -0 counts as +0.  Key 0 is
 // reserved for "not a candidate" (-inf or out of range); real candidates map to >= 1.
 __device__ __forceinline__ uint32_t ordered_key(float s) {
@@ -455,12 +505,8 @@ __device__ __forceinline__ void find_bin(const uint32_t* hist, uint32_t* bcast, 
   const uint32_t c0 = hist[4 * lane + 0], c1 = hist[4 * lane + 1];
   const uint32_t c2 = hist[4 * lane + 2], c3 = hist[4 * lane + 3];
   const uint32_t s = c0 + c1 + c2 + c3;
-  uint32_t S = s;   // inclusive suffix sum over lanes
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t v = __shfl_down(S, off);
-    if (lane + off < 64) S += v;
-  }
+  const uint32_t total = wave_sum(s);
+  const uint32_t S = total - wave_scan_add(s) + s;   // inclusive suffix sum over lanes
   const uint32_t a3 = S - s, a2 = a3 + c3, a1 = a2 + c2, a0 = a1 + c1;
   int dsel = -1;
   uint32_t above = 0, mine = 0;
@@ -473,10 +519,10 @@ __device__ __forceinline__ void find_bin(const uint32_t* hist, uint32_t* bcast, 
     bcast[1] = krem - above;
     bcast[2] = mine;
   }
-  if (lane == 0 && krem > S) {
+  if (lane == 0 && krem > total) {
     bcast[0] = 0xffffffffu;
-    bcast[1] = krem - S;
-    bcast[2] = S;
+    bcast[1] = krem - total;
+    bcast[2] = total;
   }
 }
 
@@ -552,15 +598,11 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
   uint32_t lo_est = t_min >= TOP - 1u ? 0u : t_min + 1u;   // this thread's minimum, 0 if it has none
   uint32_t k_min = t_min >= TOP - 1u ? TOP : t_min + 1u;
   uint32_t k_max = t_max <= 1u ? 0u : t_max - 1u;
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    cnt += __shfl_xor(cnt, off);
-    n_top += __shfl_xor(n_top, off);
-    const uint32_t a = __shfl_xor(lo_est, off), b = __shfl_xor(k_min, off), c = __shfl_xor(k_max, off);
-    lo_est = a > lo_est ? a : lo_est;
-    k_min = b < k_min ? b : k_min;
-    k_max = c > k_max ? c : k_max;
-  }
+  cnt = wave_sum(cnt);
+  n_top = wave_sum(n_top);
+  lo_est = wave_max(lo_est);
+  k_min = wave_min(k_min);
+  k_max = wave_max(k_max);
   if (lane == 0) {
     sm.red[wave] = cnt;
     sm.red[NW + wave] = n_top;
@@ -658,15 +700,7 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
     g_cnt += key[j] > tau;
     e_cnt += (tau != 0u && key[j] == tau);
   }
-  uint32_t g_inc = g_cnt, e_inc = e_cnt;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t vg = __shfl_up(g_inc, off), ve = __shfl_up(e_inc, off);
-    if (lane >= off) {
-      g_inc += vg;
-      e_inc += ve;
-    }
-  }
+  const uint32_t g_inc = wave_scan_add(g_cnt), e_inc = wave_scan_add(e_cnt);
   __syncthreads();   // sm.red is free again
   if (lane == 63) {
     sm.red[wave] = g_inc;

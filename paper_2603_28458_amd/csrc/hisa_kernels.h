@@ -10,18 +10,21 @@
 namespace hisa {
 
 // Fused Stage 2 kernel: waves per query and LDS tiles per wave.  Measured at the 64K bf16 prefill:
-// 4 waves x 1 tile (two workgroups per CU) 9.6 ms; 8 waves x 1 or 2 tiles (one workgroup per CU,
-// the select no longer overlaps another query's scoring) 12.0 ms; 6 waves under a 168-register cap
-// (three waves per SIMD, one accumulator live, no overlap inside a wave, no spills) 13.6 ms: the
+// 4 waves x 1 tile (two workgroups per CU) 8.9 ms; 8 waves x 1 or 2 tiles (one workgroup per CU,
+// the select no longer overlaps another query's scoring) +25 %; 6 waves under a 168-register cap
+// (three waves per SIMD, one accumulator live, no overlap inside a wave, no spills) +40 %: the
 // MFMA-over-epilogue overlap inside a wave is worth more than a third wave.  Deeper rings do not
 // help, neither do LDS reads requested half a tile early, a branch-free step with one DMA
 // instruction per MFMA pair, a raised wave priority over the MFMAs, or touching the lines of the
 // tiles two ahead (all within 2 % or slower), or a fixed grid of workgroups that each walk several
-// queries (10.6 ms with 512 workgroups: the hardware's dynamic placement of one short workgroup
+// queries (+10 % with 512 workgroups: the hardware's dynamic placement of one short workgroup
 // per query balances better): with bf16 keys a tile is 8 KB through the CU's
 // vector-memory path per 16 MFMAs, and that path (about 44 B/clk/CU measured, keys L2-resident)
-// saturates together with the matrix cores; with fp8 keys the widening puts the step just past
-// the rate at which vector instructions still issue under the MFMAs.
+// saturates together with the matrix cores.  fp8 keys run on the fp8 MFMA against the two-term
+// e4m3 form of the query (no widening instructions, half the tile bytes): 7.7 ms; a ring of two
+// fp8 tiles with the operand reads of tile j+1 requested before the MFMAs of tile j and awaited
+// after them measured the same, and time grows by 1.5 ms per 16 kept blocks on top of 1.5 ms that
+// does not depend on m (per query: fragment load and split, block table, top-k, output).
 constexpr int kNBuf = 1;
 constexpr int kFusedWaves = 4;
 
@@ -513,13 +516,13 @@ __global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
   __amdgpu_buffer_rsrc_t krsrc, srsrc;
   key_buffers<KDT>(a, seq, krsrc, srsrc);
   const uint32_t ring_addr = lds_address(ring) + wave * NB * TileGeom<KDT>::kBufBytes;
-  wave_pipeline<HG, KDT, NB>(
-      fo, krsrc, srsrc, ring_addr, nj, [&](int j) { return rows.at(j); },
-      [&](int j, float s) {
-        const int row = rows.at(j) + (lane & 31);
-        if (row >= n_vis) s = neg_inf();
-        if (lane < 32 && (gather || row < n_vis)) out[outs.at(j) + lane] = s;
-      });
+  auto row_at = [&](int j) { return rows.at(j); };
+  auto finish = [&](int j, float s) {
+    const int row = rows.at(j) + (lane & 31);
+    if (row >= n_vis) s = neg_inf();
+    if (lane < 32 && (gather || row < n_vis)) out[outs.at(j) + lane] = s;
+  };
+  wave_pipeline<HG, KDT, NB>(fo, krsrc, srsrc, ring_addr, nj, row_at, finish);
 }
 
 // Eq. 1 / Eq. 5 on MFMA for a causal prefill of ONE sequence with consecutive positions: one
@@ -894,12 +897,8 @@ __global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(Sel
         kmax = key > kmax ? key : kmax;
       }
     }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-      const uint32_t lo = __shfl_xor(kmin, off), hi = __shfl_xor(kmax, off);
-      kmin = lo < kmin ? lo : kmin;
-      kmax = hi > kmax ? hi : kmax;
-    }
+    kmin = wave_min(kmin);
+    kmax = wave_max(kmax);
     if (lane == 0) {
       tot[wave] = kmin;
       tot[NW + wave] = kmax;
@@ -954,13 +953,9 @@ __global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(Sel
     static_assert(NBIN == 4 * THREADS, "four bins per thread");
     const uint32_t c0 = hist[4 * tid + 0], c1 = hist[4 * tid + 1], c2 = hist[4 * tid + 2], c3 = hist[4 * tid + 3];
     const uint32_t mine = c0 + c1 + c2 + c3;
-    uint32_t S = mine;   // inclusive suffix sum over the lanes of the wave
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t v = __shfl_down(S, off);
-      if (lane + off < 64) S += v;
-    }
-    if (lane == 0) tot[wave] = S;
+    const uint32_t wave_total = wave_sum(mine);
+    uint32_t S = wave_total - wave_scan_add(mine) + mine;   // inclusive suffix sum over the lanes of the wave
+    if (lane == 0) tot[wave] = wave_total;
     __syncthreads();
     uint32_t total = 0;
 #pragma unroll
@@ -1038,12 +1033,7 @@ __global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(Sel
       cc += is_c[x];
     }
     const uint32_t packed = cs | (cc << 16);
-    uint32_t inc = packed;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t v = __shfl_up(inc, off);
-      if (lane >= off) inc += v;
-    }
+    const uint32_t inc = wave_scan_add(packed);
     if (lane == 63) tot[par * NW + wave] = inc;
     __syncthreads();
     uint32_t before = 0, chunk = 0;
@@ -1232,12 +1222,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
     const int blk = blk_ids[i];
     if (blk >= 0 && blk < n_blocks) n_used = i + 1;
   }
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    const int o = __shfl_xor(n_used, off);
-    n_used = o > n_used ? o : n_used;
-  }
-  const int n_active = __builtin_amdgcn_readfirstlane(n_used) * tpb;
+  const int n_active = __builtin_amdgcn_readfirstlane((int)wave_max((uint32_t)n_used)) * tpb;
   // first key row of tile v, or -1 if its slot is empty / out of range / not visible
   auto row_of = [&](int v) -> int {
     const int slot = v / tpb;
@@ -1282,19 +1267,35 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
   const bool one_slot = a.B % E == 0;
   const int my_slot = (int)(threadIdx.x * E) / a.B;
   const int my_base = (one_slot && my_slot < a.m) ? (blk_ids[my_slot] - my_slot) * a.B : 0;
+  // The selected indices are collected in LDS and leave as whole 16-byte rows: written straight
+  // from the select, a wave's store would scatter a dozen dwords over as many cache lines.  The
+  // score area serves as the collection buffer: by the time the select emits (after its last
+  // barrier) every thread holds its candidates in registers and the scores are dead; k <= m * B.
+  // (The optional score output keeps the direct path.)
+  int32_t* stage = reinterpret_cast<int32_t*>(sc);
   auto emit = [&](int p, int i, uint32_t key) {
+    int tok;
     if (one_slot) {
-      oi[p] = my_base + i;
+      tok = my_base + i;
     } else {
       const int slot = i / a.B;
-      oi[p] = blk_ids[slot] * a.B + (i - slot * a.B);
+      tok = blk_ids[slot] * a.B + (i - slot * a.B);
     }
+    stage[p] = tok;
     if (os) os[p] = key_to_score(key);
   };
   const int n_out = select_topk<NT, E>(sm, n_cand_slots, k, load4, load1, emit);
   for (int p = n_out + threadIdx.x; p < k; p += NT) {
-    oi[p] = -1;
+    stage[p] = -1;
     if (os) os[p] = neg_inf();
+  }
+  __syncthreads();
+  if ((k & 3) == 0 && (reinterpret_cast<uintptr_t>(oi) & 15) == 0) {
+    const int4* src = reinterpret_cast<const int4*>(stage);
+    int4* dst = reinterpret_cast<int4*>(oi);
+    for (int p = threadIdx.x; p < (k >> 2); p += NT) dst[p] = src[p];
+  } else {
+    for (int p = threadIdx.x; p < k; p += NT) oi[p] = stage[p];
   }
 }
 
