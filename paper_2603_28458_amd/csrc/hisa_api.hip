@@ -150,6 +150,9 @@ int launch_select(const SelectArgs& a, int rows, int n_max, hipStream_t st) {
     hipLaunchKernelGGL((k_select<64, 8, MAP>), grid, dim3(64), 0, st, a);
   else if (n_max <= 2048)
     hipLaunchKernelGGL((k_select<256, 8, MAP>), grid, dim3(256), 0, st, a);
+  else if (n_max <= 8192 && rows * a.n_seg <= 256)
+    // a decode batch: most CUs idle anyway, so a row gets 16 waves and a quarter of the work per thread
+    hipLaunchKernelGGL((k_select<1024, 8, MAP>), grid, dim3(1024), 0, st, a);
   else if (n_max <= 8192)
     hipLaunchKernelGGL((k_select<256, 32, MAP>), grid, dim3(256), 0, st, a);
   else if (n_max <= 16384)

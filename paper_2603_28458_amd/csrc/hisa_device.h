@@ -40,6 +40,56 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint4 u) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Wave64 reductions and scans on the DPP / lane-swap paths of the vector ALU (a __shfl goes
+// through the LDS crossbar and costs a memory-latency round trip per step).
+template <int CTRL, int ROW_MASK = 0xf, int BANK_MASK = 0xf>
+__device__ __forceinline__ uint32_t dpp_or0(uint32_t v) {   // lanes without a source read 0
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, BANK_MASK, false);
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_perm(uint32_t v) {  // permutations: every lane has a source
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+}
+
+// op (associative, commutative) over all 64 lanes, result in every lane.
+template <class Op>
+__device__ __forceinline__ uint32_t wave_all(uint32_t v, Op op) {
+  v = op(v, dpp_perm<0xB1>(v));    // quad_perm [1,0,3,2]
+  v = op(v, dpp_perm<0x4E>(v));    // quad_perm [2,3,0,1]
+  v = op(v, dpp_perm<0x141>(v));   // row_half_mirror
+  v = op(v, dpp_perm<0x140>(v));   // row_mirror
+  {
+    const auto sw = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = op((uint32_t)sw[0], (uint32_t)sw[1]);
+  }
+  {
+    const auto sw = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    v = op((uint32_t)sw[0], (uint32_t)sw[1]);
+  }
+  return v;
+}
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+  return wave_all(v, [](uint32_t a, uint32_t b) { return a + b; });
+}
+__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
+  return wave_all(v, [](uint32_t a, uint32_t b) { return a > b ? a : b; });
+}
+__device__ __forceinline__ uint32_t wave_min(uint32_t v) {
+  return wave_all(v, [](uint32_t a, uint32_t b) { return a < b ? a : b; });
+}
+
+// Inclusive prefix sum over the 64 lanes.
+__device__ __forceinline__ uint32_t wave_scan_add(uint32_t v) {
+  v += dpp_or0<0x111>(v);        // row_shr:1
+  v += dpp_or0<0x112>(v);        // row_shr:2
+  v += dpp_or0<0x114>(v);        // row_shr:4
+  v += dpp_or0<0x118>(v);        // row_shr:8
+  v += dpp_or0<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+  v += dpp_or0<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
+// ------------------------------------------------------------------------------------------
 // Query fragment: all H = 32*HG heads of one query in MFMA A-operand layout, plus the gates in
 // the accumulator's row layout.  A operand of v_mfma_f32_32x32x16_bf16: lane l supplies row
 // (l % 32) and the 8 contraction elements of half (l / 32); step kk covers d = 16*kk .. 16*kk+15.
@@ -260,6 +310,97 @@ __device__ __forceinline__ void split_qfrag(const QFrag<HG>& f, QFrag8<HG>& o) {
   }
 }
 
+// The same two-term fragment built ONCE per workgroup of NW waves instead of once per wave: wave w
+// converts the heads w*H/NW .. (w+1)*H/NW - 1 (a head is spread over 64*NW/H consecutive lanes, so
+// its largest magnitude is a DPP reduction inside a row), writes hi / lo in operand order and the
+// scaled gates to LDS, and after one barrier every wave reads the whole fragment (16 reads of 16
+// bytes, lane-contiguous).  lds: 32*HG*260 bytes that nothing else touches until the function
+// returns (it ends with a second barrier).  q, w: this query's [H, d] bf16 and [H] gates.
+template <int HG, int NW>
+__device__ __forceinline__ void split_query_shared(const uint16_t* __restrict__ q, const float* __restrict__ w,
+                                                   unsigned char* lds, int wave, QFrag8<HG>& o) {
+  constexpr int H = 32 * HG;
+  constexpr int HP = H / NW;     // heads per wave
+  constexpr int LPH = 64 / HP;   // lanes per head
+  constexpr int EPL = kD / LPH;  // elements per lane
+  static_assert(H % NW == 0 && (LPH == 4 || LPH == 8 || LPH == 16), "a head must map to 4, 8 or 16 lanes");
+  const int lane = lane_id();
+  const int head = wave * HP + lane / LPH, seg = lane % LPH;
+  uint4 v[EPL / 8];
+  const uint4* src = reinterpret_cast<const uint4*>(q + head * kD + seg * EPL);
+#pragma unroll
+  for (int c = 0; c < EPL / 8; ++c) v[c] = src[c];
+  const float gate = w[head];
+  uint32_t mag = 0;
+#pragma unroll
+  for (int c = 0; c < EPL / 8; ++c) {
+    const uint32_t d[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const uint32_t lo16 = d[x] & 0x7fffu, hi16 = (d[x] >> 16) & 0x7fffu;
+      mag = mag > lo16 ? mag : lo16;
+      mag = mag > hi16 ? mag : hi16;
+    }
+  }
+  auto mx = [](uint32_t a, uint32_t b) { return a > b ? a : b; };
+  mag = mx(mag, dpp_perm<0xB1>(mag));                  // 2 lanes
+  mag = mx(mag, dpp_perm<0x4E>(mag));                  // 4
+  if (LPH >= 8) mag = mx(mag, dpp_perm<0x141>(mag));   // 8
+  if (LPH >= 16) mag = mx(mag, dpp_perm<0x140>(mag));  // 16
+  int e = (int)(mag >> 7);
+  e = e < 8 ? 8 : (e > 254 ? 254 : e);
+  const float up = __uint_as_float((uint32_t)(261 - e) << 23);
+  const float down = __uint_as_float((uint32_t)(e - 7) << 23);
+  const int g = head >> 5, r = head & 31;
+  uint2* frag = reinterpret_cast<uint2*>(lds);
+  float* gates = reinterpret_cast<float*>(lds + 32 * HG * 256);
+#pragma unroll
+  for (int c = 0; c < EPL / 8; ++c) {
+    const uint32_t d[4] = {v[c].x, v[c].y, v[c].z, v[c].w};
+    int whi[2] = {0, 0}, wlo[2] = {0, 0};
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const float x0 = __uint_as_float(d[x] << 16) * up;
+      const float x1 = __uint_as_float(d[x] & 0xffff0000u) * up;
+      const int h = __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, 0, false);
+      const auto back = __builtin_amdgcn_cvt_pk_f32_fp8(h, false);
+      const int l = __builtin_amdgcn_cvt_pk_fp8_f32(x0 - back[0], x1 - back[1], 0, false);
+      whi[x >> 1] |= (h & 0xffff) << (16 * (x & 1));
+      wlo[x >> 1] |= (l & 0xffff) << (16 * (x & 1));
+    }
+    // chunk c8 of the head = elements 8*c8 .. 8*c8+7 = contraction step kk = c8 / 2, lane half c8 % 2
+    const int c8 = seg * (EPL / 8) + c;
+    const int kk = c8 >> 1, half = c8 & 1;
+    // operand order: [g][ks = kk / 4][piece][lane = half*32 + r] x 32 bytes, 8 bytes per kk % 4
+    const int slot = (((g * 2 + (kk >> 2)) * 2) * 64 + half * 32 + r) * 4 + (kk & 3);
+    frag[slot] = make_uint2((uint32_t)whi[0], (uint32_t)whi[1]);
+    frag[slot + 64 * 4] = make_uint2((uint32_t)wlo[0], (uint32_t)wlo[1]);
+  }
+  if (seg == 0) gates[head] = gate * down;
+  __syncthreads();
+  const int my_half = lane >> 5;
+#pragma unroll
+  for (int gg = 0; gg < HG; ++gg) {
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const uint4* ph = reinterpret_cast<const uint4*>(lds + ((((gg * 2 + ks) * 2 + 0) * 64 + lane) * 32));
+      const uint4* pl = reinterpret_cast<const uint4*>(lds + ((((gg * 2 + ks) * 2 + 1) * 64 + lane) * 32));
+      const uint4 h0 = ph[0], h1 = ph[1], l0 = pl[0], l1 = pl[1];
+      o.hi[gg][ks] = i32x8{(int)h0.x, (int)h0.y, (int)h0.z, (int)h0.w, (int)h1.x, (int)h1.y, (int)h1.z, (int)h1.w};
+      o.lo[gg][ks] = i32x8{(int)l0.x, (int)l0.y, (int)l0.z, (int)l0.w, (int)l1.x, (int)l1.y, (int)l1.z, (int)l1.w};
+    }
+#pragma unroll
+    for (int a4 = 0; a4 < 4; ++a4) {
+      const float4 gv = *reinterpret_cast<const float4*>(gates + gg * 32 + 8 * a4 + 4 * my_half);
+      o.w[gg][4 * a4 + 0] = gv.x;
+      o.w[gg][4 * a4 + 1] = gv.y;
+      o.w[gg][4 * a4 + 2] = gv.z;
+      o.w[gg][4 * a4 + 3] = gv.w;
+    }
+  }
+  __syncthreads();
+}
+
 template <int HG>
 __device__ __forceinline__ accvec<HG> mfma_tile(const QFrag8<HG>& f, const u32x16& kv) {
   f32x16 acc[HG];
@@ -408,55 +549,40 @@ __device__ __forceinline__ void wait_vmem_le() {
   __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
 }
 
-// ------------------------------------------------------------------------------------------
-// Wave64 reductions and scans on the DPP / lane-swap paths of the vector ALU (a __shfl goes
-// through the LDS crossbar and costs a memory-latency round trip per step).
-template <int CTRL, int ROW_MASK = 0xf, int BANK_MASK = 0xf>
-__device__ __forceinline__ uint32_t dpp_or0(uint32_t v) {   // lanes without a source read 0
-  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, BANK_MASK, false);
-}
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_perm(uint32_t v) {  // permutations: every lane has a source
-  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+// The bf16 query fragment through LDS, loaded ONCE per workgroup of NW waves: the 32 heads of a
+// group are 32 rows of 256 bytes, the geometry of a key tile, and the MFMA A operand of lane
+// (row, half) at step kk is chunk 2*kk + half of its row, which is what lds_read_tile_raw returns.
+// lds: HG * 8192 bytes nothing else touches until the function returns (it ends with a barrier).
+template <int HG, int NW>
+__device__ __forceinline__ void load_qfrag_shared(QFrag<HG>& f, const uint16_t* __restrict__ q,
+                                                  const float* __restrict__ w, long q_bytes_left,
+                                                  uint32_t lds_addr, int wave) {
+  const int lane = lane_id();
+  const int half = lane >> 5;
+  const __amdgpu_buffer_rsrc_t qrsrc = key_buffer(q, q_bytes_left);
+  const u32x8 lane_offs = tile_lane_offsets_bf16();
+  // the 8 * HG transfers of 1 KB are dealt round robin to the waves
+#pragma unroll
+  for (int i = 0; i < 8 * HG; ++i)
+    if (i % NW == wave)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(qrsrc, (lds_void*)(uintptr_t)(lds_addr + i * 1024), 16,
+                                               (int)lane_offs[i & 7], (i >> 3) * 8192, 0, 0);
+#pragma unroll
+  for (int g = 0; g < HG; ++g)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) f.w[g][i] = w[g * 32 + 8 * (i >> 2) + 4 * half + (i & 3)];
+  wait_vmem_le<0>();
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < HG; ++g) {
+    const u32x32 t = lds_read_tile_raw(lds_addr + g * 8192);
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+      f.a[g][kk] = as_bf16x8(make_uint4(t[4 * kk + 0], t[4 * kk + 1], t[4 * kk + 2], t[4 * kk + 3]));
+  }
+  __syncthreads();
 }
 
-// op (associative, commutative) over all 64 lanes, result in every lane.
-template <class Op>
-__device__ __forceinline__ uint32_t wave_all(uint32_t v, Op op) {
-  v = op(v, dpp_perm<0xB1>(v));    // quad_perm [1,0,3,2]
-  v = op(v, dpp_perm<0x4E>(v));    // quad_perm [2,3,0,1]
-  v = op(v, dpp_perm<0x141>(v));   // row_half_mirror
-  v = op(v, dpp_perm<0x140>(v));   // row_mirror
-  {
-    const auto sw = __builtin_amdgcn_permlane16_swap(v, v, false, false);
-    v = op((uint32_t)sw[0], (uint32_t)sw[1]);
-  }
-  {
-    const auto sw = __builtin_amdgcn_permlane32_swap(v, v, false, false);
-    v = op((uint32_t)sw[0], (uint32_t)sw[1]);
-  }
-  return v;
-}
-__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
-  return wave_all(v, [](uint32_t a, uint32_t b) { return a + b; });
-}
-__device__ __forceinline__ uint32_t wave_max(uint32_t v) {
-  return wave_all(v, [](uint32_t a, uint32_t b) { return a > b ? a : b; });
-}
-__device__ __forceinline__ uint32_t wave_min(uint32_t v) {
-  return wave_all(v, [](uint32_t a, uint32_t b) { return a < b ? a : b; });
-}
-
-// Inclusive prefix sum over the 64 lanes.
-__device__ __forceinline__ uint32_t wave_scan_add(uint32_t v) {
-  v += dpp_or0<0x111>(v);        // row_shr:1
-  v += dpp_or0<0x112>(v);        // row_shr:2
-  v += dpp_or0<0x114>(v);        // row_shr:4
-  v += dpp_or0<0x118>(v);        // row_shr:8
-  v += dpp_or0<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
-  v += dpp_or0<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
-  return v;
-}
 
 // ------------------------------------------------------------------------------------------
 // Order-preserving key of a score: larger score <=> larger key.  -0 counts as +0.  Key 0 is

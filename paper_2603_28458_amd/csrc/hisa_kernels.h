@@ -1170,8 +1170,15 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
   const int pos = query_pos(a, t, seq);
   const int n_vis = pos + 1;
 
+  // fp8 keys without Stage 1 in this launch: no wave needs the bf16 fragment, and the two-term
+  // e4m3 fragment is built once for the workgroup (below) instead of once per wave
+  constexpr bool kSharedSplit = KDT == DT_FP8 && E1 == 0;
+  static_assert(!kSharedSplit || kStageBytes >= (size_t)32 * HG * 260, "the shared fragment is built in the rings");
+  static_assert(kStageBytes >= (size_t)HG * 8192, "the shared query fragment is staged in the rings");
   QFrag<HG> f;
-  load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
+  if constexpr (!kSharedSplit)
+    load_qfrag_shared<HG, NW>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H,
+                              (long)a.H * kD * 2, lds_address(smem), wave);
 
   const int tpb = a.B >> 5;
   const int n_blocks = (int)(a.rows_per_seq / a.B);
@@ -1235,9 +1242,13 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
   LaneTable rows;
   rows.lo = row_of(wave + NW * (lane < nj ? lane : 0));
   rows.hi = (nj > 64) ? row_of(wave + NW * (lane + 64 < nj ? lane + 64 : 0)) : -1;
-  qfrag_ready<HG>(f);
   typename Operands<HG, KDT>::Frag fo;
-  Operands<HG, KDT>::make(f, fo);
+  if constexpr (kSharedSplit) {
+    split_query_shared<HG, NW>((const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H, smem, wave, fo);
+  } else {
+    qfrag_ready<HG>(f);
+    Operands<HG, KDT>::make(f, fo);
+  }
   __amdgpu_buffer_rsrc_t krsrc, srsrc;
   key_buffers<KDT>(a, seq, krsrc, srsrc);
   auto row_at = [&](int j) {
