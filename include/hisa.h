@@ -203,9 +203,12 @@ int hisa_index_iou(const int32_t* a_idx, const int32_t* b_idx, int32_t T, int32_
  * the HBM rate this chip sustains.  hisa_probe_mfma: 512 workgroups of 4 waves each issue
  * iters * 16 v_mfma_f32_32x32x16_bf16 and nothing else; *flop (host) receives the flop count of the
  * launch, out (device, 512 * 256 floats) receives values that only keep the loop alive.
+ * hisa_probe_mfma_fp8: the same with iters * 8 v_mfma_f32_32x32x64_f8f6f4 (e4m3 x e4m3), the
+ * instruction the fp8-key scoring runs on.
  */
 int hisa_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 int hisa_probe_mfma(float* out, int32_t iters, double* flop, void* stream);
+int hisa_probe_mfma_fp8(float* out, int32_t iters, double* flop, void* stream);
 
 /* Recommended workspace size in bytes for `op` (HISA_OP_*) at these shapes; 0 if none is needed
  * or the shapes are invalid.  `want_scores` != 0: the optional full score output of Stage 1 / 2

@@ -399,6 +399,15 @@ int hisa_probe_mfma(float* out, int32_t iters, double* flop, void* stream) {
   return launch_status();
 }
 
+int hisa_probe_mfma_fp8(float* out, int32_t iters, double* flop, void* stream) {
+  if (!out || !flop) return HISA_ERR_NULL;
+  if (iters < 1) return HISA_ERR_SHAPE;
+  const int wgs = 512;
+  hipLaunchKernelGGL(k_probe_mfma_fp8, dim3(wgs), dim3(256), 0, (hipStream_t)stream, out, iters);
+  *flop = (double)wgs * 4.0 * iters * 8.0 * (2.0 * 32 * 32 * 64);
+  return launch_status();
+}
+
 int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, const void* pooled,
                           int32_t pooled_dtype, int32_t B, int32_t m, int32_t* block_idx,
                           float* block_scores, void* ws, size_t ws_bytes, void* stream) {
@@ -425,11 +434,6 @@ int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, co
     J = (float*)ws;
   }
   hipStream_t s = (hipStream_t)stream;
-  if (block_scores) {
-    const long n = (long)T * M;
-    hipLaunchKernelGGL(k_fill_f32, dim3((unsigned)((n + 255) / 256 > 4096 ? 4096 : (n + 255) / 256)),
-                       dim3(256), 0, s, J, n, -__builtin_inff());
-  }
   ScoreArgs a = base_args(queries, keys);
   a.keys = pooled;
   a.k_scale = nullptr;
@@ -439,6 +443,11 @@ int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, co
   a.ld = M;
   a.t_begin = 0;
   a.t_count = T;
+  if (block_scores) {
+    const long n = (long)T * M;
+    hipLaunchKernelGGL(k_fill_f32, dim3((unsigned)((n + 255) / 256 > 4096 ? 4096 : (n + 255) / 256)),
+                       dim3(256), 0, s, J, n, -__builtin_inff());
+  }
   launch_score(path, pooled_dtype, a, M, !queries->q_seq && !queries->q_pos, s);
 
   SelectArgs sa = select_base(queries, keys);

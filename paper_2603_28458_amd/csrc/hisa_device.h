@@ -281,26 +281,47 @@ __device__ __forceinline__ void split_qfrag(const QFrag<HG>& f, QFrag8<HG>& o) {
     e = e < 8 ? 8 : (e > 254 ? 254 : e);      // (rows below 2^-119 lose their low bits: they score ~0)
     const float up = __uint_as_float((uint32_t)(261 - e) << 23);     // 2^(134 - e)
     const float down = __uint_as_float((uint32_t)(e - 7) << 23);     // 2^(e - 134)
+    uint32_t whi[8][2], wlo[8][2];   // [kk]: the 8 codes of d = 16*kk + 8*half .. +7
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       Pack128 p;
       p.v = f.a[g][kk];
       const uint32_t d[4] = {p.u.x, p.u.y, p.u.z, p.u.w};
-      int whi[2] = {0, 0}, wlo[2] = {0, 0};
+      whi[kk][0] = whi[kk][1] = wlo[kk][0] = wlo[kk][1] = 0u;
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const float x0 = __uint_as_float(d[c] << 16) * up;
         const float x1 = __uint_as_float(d[c] & 0xffff0000u) * up;
-        int h = __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, 0, false);
+        const int h = __builtin_amdgcn_cvt_pk_fp8_f32(x0, x1, 0, false);
         const auto back = __builtin_amdgcn_cvt_pk_f32_fp8(h, false);
         const int l = __builtin_amdgcn_cvt_pk_fp8_f32(x0 - back[0], x1 - back[1], 0, false);
-        whi[c >> 1] |= (h & 0xffff) << (16 * (c & 1));
-        wlo[c >> 1] |= (l & 0xffff) << (16 * (c & 1));
+        whi[kk][c >> 1] |= (uint32_t)(h & 0xffff) << (16 * (c & 1));
+        wlo[kk][c >> 1] |= (uint32_t)(l & 0xffff) << (16 * (c & 1));
       }
-      o.hi[g][kk >> 2][2 * (kk & 3) + 0] = whi[0];
-      o.hi[g][kk >> 2][2 * (kk & 3) + 1] = whi[1];
-      o.lo[g][kk >> 2][2 * (kk & 3) + 0] = wlo[0];
-      o.lo[g][kk >> 2][2 * (kk & 3) + 1] = wlo[1];
+    }
+    // From halves of every 16-element chunk (the bf16 fragment's order) to whole chunks: for the
+    // chunk pair (2j, 2j+1) lanes 0-31 hand the first half of the odd chunk to lanes 32-63 and
+    // receive the second half of the even chunk: afterwards a lane of half h holds chunk 2j + h.
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        const auto sh = __builtin_amdgcn_permlane32_swap(whi[2 * j][x], whi[2 * j + 1][x], false, false);
+        const auto sl = __builtin_amdgcn_permlane32_swap(wlo[2 * j][x], wlo[2 * j + 1][x], false, false);
+        whi[2 * j][x] = sh[0];
+        whi[2 * j + 1][x] = sh[1];
+        wlo[2 * j][x] = sl[0];
+        wlo[2 * j + 1][x] = sl[1];
+      }
+      // chunk 2j + half as 16 bytes: (first half, second half) = (entry 2j, entry 2j+1)
+      o.hi[g][j >> 1][4 * (j & 1) + 0] = (int)whi[2 * j][0];
+      o.hi[g][j >> 1][4 * (j & 1) + 1] = (int)whi[2 * j][1];
+      o.hi[g][j >> 1][4 * (j & 1) + 2] = (int)whi[2 * j + 1][0];
+      o.hi[g][j >> 1][4 * (j & 1) + 3] = (int)whi[2 * j + 1][1];
+      o.lo[g][j >> 1][4 * (j & 1) + 0] = (int)wlo[2 * j][0];
+      o.lo[g][j >> 1][4 * (j & 1) + 1] = (int)wlo[2 * j][1];
+      o.lo[g][j >> 1][4 * (j & 1) + 2] = (int)wlo[2 * j + 1][0];
+      o.lo[g][j >> 1][4 * (j & 1) + 3] = (int)wlo[2 * j + 1][1];
     }
     // the gate of accumulator register i belongs to head row 8*(i/4) + 4*half + i%4, whose
     // power of two sits in the lane of that number
@@ -368,11 +389,12 @@ __device__ __forceinline__ void split_query_shared(const uint16_t* __restrict__ 
       whi[x >> 1] |= (h & 0xffff) << (16 * (x & 1));
       wlo[x >> 1] |= (l & 0xffff) << (16 * (x & 1));
     }
-    // chunk c8 of the head = elements 8*c8 .. 8*c8+7 = contraction step kk = c8 / 2, lane half c8 % 2
+    // elements 8*c8 .. 8*c8+7 of the head = half c8 % 2 of the 16-element chunk ch = c8 / 2, which
+    // belongs to lane half ch % 2 as its chunk j = ch / 2 (see lds_read_tile_fp8_raw)
     const int c8 = seg * (EPL / 8) + c;
-    const int kk = c8 >> 1, half = c8 & 1;
-    // operand order: [g][ks = kk / 4][piece][lane = half*32 + r] x 32 bytes, 8 bytes per kk % 4
-    const int slot = (((g * 2 + (kk >> 2)) * 2) * 64 + half * 32 + r) * 4 + (kk & 3);
+    const int ch = c8 >> 1, half = ch & 1, j = ch >> 1;
+    // operand order: [g][ks = j / 2][piece][lane = half*32 + r] x 32 bytes, 8 bytes per (j % 2, c8 % 2)
+    const int slot = (((g * 2 + (j >> 1)) * 2) * 64 + half * 32 + r) * 4 + (j & 1) * 2 + (c8 & 1);
     frag[slot] = make_uint2((uint32_t)whi[0], (uint32_t)whi[1]);
     frag[slot + 64 * 4] = make_uint2((uint32_t)wlo[0], (uint32_t)wlo[1]);
   }
@@ -485,53 +507,54 @@ __device__ __forceinline__ void tile_dma_bf16(__amdgpu_buffer_rsrc_t rsrc, uint3
 }
 
 // fp8 keys by DMA: the 4 KB of a tile as 256 chunks of 16 codes; LDS chunk p = i*64 + lane holds
-// global chunk (row r = p / 8, column (p % 8) xor (r % 8)), so the 8-byte MFMA-layout reads
-// below spread over the banks.  A fifth transfer brings the 32 per-token scales (as 64 floats).
+// global chunk (row r = p / 8, column (p % 8) xor ((r / 2) % 8)): 16 consecutive rows of one
+// column then cover all 64 banks, which is what the 16-byte MFMA-layout reads below need (rows are
+// 128 bytes, so two neighbours share the swizzle and differ in the upper half of the banks).
+// A fifth transfer brings the 32 per-token scales (as 64 floats).
 __device__ __forceinline__ void tile_dma_fp8(__amdgpu_buffer_rsrc_t rsrc, __amdgpu_buffer_rsrc_t srsrc,
                                              uint32_t lds_addr, int row0) {
   const int lane = lane_id();
-  const int voff = (lane >> 3) * 128 + (((lane & 7) ^ (lane >> 3)) << 4);
+  // row r = 8*i + lane/8, so (r/2) % 8 = (4*i + lane/16) % 8: transfers alternate between two offsets
+  const int voff0 = (lane >> 3) * 128 + (((lane & 7) ^ (lane >> 4)) << 4);
+  const int voff1 = voff0 ^ 64;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(uintptr_t)(lds_addr + i * 1024), 16, voff,
-                                             row0 * 128 + i * 1024, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void*)(uintptr_t)(lds_addr + i * 1024), 16,
+                                             (i & 1) ? voff1 : voff0, row0 * 128 + i * 1024, 0, 0);
   __builtin_amdgcn_raw_ptr_buffer_load_lds(srsrc, (lds_void*)(uintptr_t)(lds_addr + 4096), 4, lane * 4,
                                            row0 * 4, 0, 0);
 }
 
-// B operands of an fp8 tile staged by tile_dma_fp8: eight 8-byte reads per lane (raw
-// instructions, see lds_read_tile_raw); read kk brings the codes of d = 16*kk + 8*(lane/32) .. +7
-// of key row lane % 32, the order split_qfrag gives the query operand.  Complete on return.
-typedef uint32_t u32x2e __attribute__((ext_vector_type(2)));
-
+// B operands of an fp8 tile staged by tile_dma_fp8: four 16-byte reads per lane (raw
+// instructions, see lds_read_tile_raw); read j brings the codes of d = 16*(2*j + lane/32) .. +15 of
+// key row lane % 32 -- lanes 0-31 take the even 16-element chunks, lanes 32-63 the odd ones, the
+// order split_qfrag gives the query operand.  Conflict-free.  Complete on return.
 __device__ __forceinline__ u32x16 lds_read_tile_fp8_raw(uint32_t tile_addr) {
   const int lane = lane_id();
   const int half = lane >> 5;
   const int r = lane & 31;
-  uint32_t ad[8];
+  uint32_t ad[4];
 #pragma unroll
-  for (int kk = 0; kk < 8; ++kk)
-    ad[kk] = tile_addr + (uint32_t)(r * 128 + ((kk ^ (r & 7)) << 4) + half * 8);
-  u32x2e x0, x1, x2, x3, x4, x5, x6, x7;
+  for (int j = 0; j < 4; ++j)
+    ad[j] = tile_addr + (uint32_t)(r * 128 + (((2 * j + half) ^ ((r >> 1) & 7)) << 4));
+  u32x4e x0, x1, x2, x3;
   asm volatile(
-      "ds_read_b64 %0, %8\n\t"
-      "ds_read_b64 %1, %9\n\t"
-      "ds_read_b64 %2, %10\n\t"
-      "ds_read_b64 %3, %11\n\t"
-      "ds_read_b64 %4, %12\n\t"
-      "ds_read_b64 %5, %13\n\t"
-      "ds_read_b64 %6, %14\n\t"
-      "ds_read_b64 %7, %15\n\t"
+      "ds_read_b128 %0, %4\n\t"
+      "ds_read_b128 %1, %5\n\t"
+      "ds_read_b128 %2, %6\n\t"
+      "ds_read_b128 %3, %7\n\t"
       "s_waitcnt lgkmcnt(0)"
-      : "=&v"(x0), "=&v"(x1), "=&v"(x2), "=&v"(x3), "=&v"(x4), "=&v"(x5), "=&v"(x6), "=&v"(x7)
-      : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3]), "v"(ad[4]), "v"(ad[5]), "v"(ad[6]), "v"(ad[7])
+      : "=&v"(x0), "=&v"(x1), "=&v"(x2), "=&v"(x3)
+      : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3])
       : "memory");
-  const u32x2e xs[8] = {x0, x1, x2, x3, x4, x5, x6, x7};
+  const u32x4e xs[4] = {x0, x1, x2, x3};
   u32x16 kv;
 #pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
-    kv[2 * kk + 0] = xs[kk][0];
-    kv[2 * kk + 1] = xs[kk][1];
+  for (int j = 0; j < 4; ++j) {
+    kv[4 * j + 0] = xs[j][0];
+    kv[4 * j + 1] = xs[j][1];
+    kv[4 * j + 2] = xs[j][2];
+    kv[4 * j + 3] = xs[j][3];
   }
   return kv;
 }

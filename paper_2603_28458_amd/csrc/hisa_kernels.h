@@ -259,6 +259,28 @@ __global__ __launch_bounds__(256) void k_probe_mfma(float* out, int iters) {
   out[(long)blockIdx.x * 256 + threadIdx.x] = (acc[0][0] + acc[1][5]) + (acc[2][9] + acc[3][15]);
 }
 
+__global__ __launch_bounds__(256) void k_probe_mfma_fp8(float* out, int iters) {
+  i32x8 a, b;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    a[e] = 0x38383838 + (int)(threadIdx.x & 3);   // e4m3 codes near 1.0
+    b[e] = 0x30303030 + e;
+  }
+  f32x16 acc[4];
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[n][i] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+      for (int n = 0; n < 4; ++n)
+        acc[n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[n], 0, 0, 0, 0, 0, 0);
+  }
+  out[(long)blockIdx.x * 256 + threadIdx.x] = (acc[0][0] + acc[1][5]) + (acc[2][9] + acc[3][15]);
+}
+
 __global__ __launch_bounds__(256) void k_fill_f32(float* p, long n, float v) {
   for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long)gridDim.x * 256) p[i] = v;
 }
@@ -568,7 +590,8 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
       voff[i] = (lane >> 4) * 256 + ((c ^ (r & 15)) << 4);
     }
   } else {
-    voff[0] = (lane >> 3) * 128 + (((lane & 7) ^ (lane >> 3)) << 4);
+    // transfer part_w of the sub-tile: rows 8*part_w + lane/8, swizzled by (row / 2) % 8
+    voff[0] = (lane >> 3) * 128 + (((lane & 7) ^ ((part_w * 4 + (lane >> 4)) & 7)) << 4);
   }
   auto dma_tile = [&](int it, int buf) {
     const uint32_t dst = tiles_addr + (buf * 2 + sub_w) * BB;
@@ -1138,6 +1161,52 @@ __global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(Sel
 }
 
 // ------------------------------------------------------------------------------------------
+// Stage 1 (Eqs. 5-6) of ONE query inside a workgroup of NW waves that already holds the query
+// fragment: the pooled keys (bf16, [n_seq, n_blocks, d]) of the visible blocks 0 .. b_t go through
+// the scoring pipeline in tiles of 32 (wave w takes tiles w, w + NW, ...), the block scores land
+// in sc[0 .. 32 * tiles) (-inf past b_t), select_topk keeps a.m of them with the first and the
+// query's own block forced (E1 blocks per thread: NW * 64 * E1 >= n_blocks), and the kept ids go
+// to blk_lds[0 .. a.m) ascending, -1 padded.  smem: the NW * NB tile rings of TILE bytes (reused
+// by the select).  Ends with a barrier: ids visible, score area and rings free again.
+template <int HG, int NW, int NB, int E1, int TILE>
+__device__ __forceinline__ void stage1_in_workgroup(const QFrag<HG>& f, const ScoreArgs& a, const void* pooled,
+                                                    int seq, int pos, int n_blocks, unsigned char* smem,
+                                                    float* sc, int32_t* blk_lds, int wave) {
+  constexpr int NT = NW * 64;
+  const int lane = threadIdx.x & 63;
+  const int n_bvis = pos < 0 ? 0 : pos / a.B + 1;
+  const int nt1 = (n_bvis + 31) >> 5;
+  const int nj1 = nt1 > wave ? (nt1 - wave + NW - 1) / NW : 0;
+  const __amdgpu_buffer_rsrc_t prsrc =
+      key_buffer((const char*)pooled + (long)seq * n_blocks * kD * 2, (long)n_blocks * kD * 2);
+  wave_pipeline<HG, DT_BF16, NB>(
+      f, prsrc, prsrc, lds_address(smem) + wave * NB * TILE, nj1,
+      [&](int j) { return (wave + NW * j) * 32; },
+      [&](int j, float s) {
+        const int b = (wave + NW * j) * 32 + (lane & 31);
+        if (lane < 32) sc[b] = b < n_bvis ? s : neg_inf();
+      });
+  __syncthreads();   // block scores complete, rings dead
+  {
+    SelectSmem<NT, E1>& sm1 = *reinterpret_cast<SelectSmem<NT, E1>*>(smem);
+    const int n_last = n_bvis - 1;
+    auto key_of = [&](int i, float v) -> uint32_t {
+      return (i == 0 || i == n_last) ? 0xffffffffu : ordered_key(v);   // first and own block forced
+    };
+    auto load4 = [&](int q) -> uint4 {
+      const float4 v = *reinterpret_cast<const float4*>(sc + 4 * q);
+      return make_uint4(key_of(4 * q, v.x), key_of(4 * q + 1, v.y), key_of(4 * q + 2, v.z),
+                        key_of(4 * q + 3, v.w));
+    };
+    auto load1 = [&](int i) -> uint32_t { return key_of(i, sc[i]); };
+    auto emit = [&](int p, int i, uint32_t) { blk_lds[p] = i; };
+    const int n_kept = select_topk<NT, E1>(sm1, n_bvis, a.m, load4, load1, emit);
+    for (int p = n_kept + threadIdx.x; p < a.m; p += NT) blk_lds[p] = -1;
+  }
+  __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------
 // Stage 2 fused (Eqs. 7-9): one workgroup of NW waves per query scores every tile of the kept
 // blocks into LDS and selects the top k there; only the k indices leave the CU.  E = candidates
 // per thread in the select (NW * 64 * E >= m * B).  LDS: the per-wave tile rings, then the m*B
@@ -1184,44 +1253,14 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
   const int n_blocks = (int)(a.rows_per_seq / a.B);
   const int32_t* blk_ids = a.block_idx + (long)t * a.m;
   if constexpr (E1 > 0) {
-    // ---- Stage 1: scores of the visible blocks 0 .. b_t, tiles of 32 pooled keys
+    // ---- Stage 1 (Eqs. 5-6) in this workgroup; the kept ids stay in LDS behind the score area
     int32_t* blk_lds = reinterpret_cast<int32_t*>(sc + sc_floats);
     blk_ids = blk_lds;
-    const int n_bvis = pos < 0 ? 0 : pos / a.B + 1;
-    const int nt1 = (n_bvis + 31) >> 5;
-    const int nj1 = nt1 > wave ? (nt1 - wave + NW - 1) / NW : 0;
     qfrag_ready<HG>(f);
-    const __amdgpu_buffer_rsrc_t prsrc =
-        key_buffer((const char*)pooled + (long)seq * n_blocks * kD * 2, (long)n_blocks * kD * 2);
-    wave_pipeline<HG, DT_BF16, NB>(
-        f, prsrc, prsrc, lds_address(smem) + wave * NB * kTileBytes, nj1,
-        [&](int j) { return (wave + NW * j) * 32; },
-        [&](int j, float s) {
-          const int b = (wave + NW * j) * 32 + (lane & 31);
-          if (lane < 32) sc[b] = b < n_bvis ? s : neg_inf();
-        });
-    __syncthreads();   // block scores complete, rings dead
-    {
-      SelectSmem<NT, E1 ? E1 : 4>& sm1 = *reinterpret_cast<SelectSmem<NT, E1 ? E1 : 4>*>(smem);
-      const int n_last = n_bvis - 1;
-      auto key_of = [&](int i, float v) -> uint32_t {
-        return (i == 0 || i == n_last) ? 0xffffffffu : ordered_key(v);   // first and own block forced
-      };
-      auto load4 = [&](int q) -> uint4 {
-        const float4 v = *reinterpret_cast<const float4*>(sc + 4 * q);
-        return make_uint4(key_of(4 * q, v.x), key_of(4 * q + 1, v.y), key_of(4 * q + 2, v.z),
-                          key_of(4 * q + 3, v.w));
-      };
-      auto load1 = [&](int i) -> uint32_t { return key_of(i, sc[i]); };
-      auto emit = [&](int p, int i, uint32_t) { blk_lds[p] = i; };
-      const int n_kept = select_topk<NT, E1 ? E1 : 4>(sm1, n_bvis, a.m, load4, load1, emit);
-      for (int p = n_kept + threadIdx.x; p < a.m; p += NT) blk_lds[p] = -1;
-    }
-    __syncthreads();   // kept ids visible; the score area and the rings are free again
+    stage1_in_workgroup<HG, NW, NB, E1, kTileBytes>(f, a, pooled, seq, pos, n_blocks, smem, sc, blk_lds, wave);
     if (block_idx_out)
       for (int p = threadIdx.x; p < a.m; p += NT) block_idx_out[(long)t * a.m + p] = blk_lds[p];
   }
-
   // Only the slots up to the last kept block are walked (a short prefix keeps few blocks).
   // Tile v = sub-tile v % tpb of slot v / tpb; wave w takes tiles w, w + NW, ...
   int n_used = 0;

@@ -22,7 +22,7 @@ def lib():
 def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "hisa.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b((?:hisa|dsa)_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b((?:hisa|dsa)_[a-z0-9_]+)\s*\(", header))
     assert declared == set(hisa.EXPORTS), declared ^ set(hisa.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
@@ -116,6 +116,8 @@ def test_validation_of_the_single_launch_call_and_the_probes(lib):
     assert lib.hisa_probe_copy(fake + 8, fake, 1024, None) == 6
     assert lib.hisa_probe_mfma(None, 10, C.byref(flop), None) == 1
     assert lib.hisa_probe_mfma(fake, 0, C.byref(flop), None) == 2
+    assert lib.hisa_probe_mfma_fp8(None, 10, C.byref(flop), None) == 1
+    assert lib.hisa_probe_mfma_fp8(fake, 0, C.byref(flop), None) == 2
 
 
 def test_workspace_sizes(lib):
