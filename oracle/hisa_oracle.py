@@ -25,7 +25,13 @@ Readings taken where the paper is silent (each is listed in the design notes of 
     the mean is rounded once (nearest-even) to the pooled dtype and Stage 1 reads the rounded value;
   * TopK orders by score descending, ties by lower index; with fewer candidates than the budget
     everything is selected and the output is padded with -1;
-  * -0 counts as +0.
+  * -0 counts as +0;
+  * packed sequences (Section 4.1's remark on blocks that straddle two sequences): a query may
+    carry a first visible position lo (its sequence's first token in the packed stream; 0 if not
+    given) and then sees the keys lo <= s <= p.  Blocks stay multiples of B of the packed stream; a
+    block that holds tokens of two sequences is pooled over everything it stores; the visible
+    blocks are lo // B .. p // B, of which the first and the last are forced, and Stage 2 masks
+    the tokens below lo.
 
 Stored formats: "f32" float32; "bf16" uint16 bit patterns (upper half of a float32); "fp8_e4m3"
 uint8 OCP e4m3fn codes with one float32 scale per token, key = scale * decode(code).
@@ -133,23 +139,24 @@ def top_select(scores: np.ndarray, ids: np.ndarray, budget: int) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------- Stage 1
-def select_blocks(J: np.ndarray, m: int) -> np.ndarray:
+def select_blocks(J: np.ndarray, m: int, b0: int = 0) -> np.ndarray:
     """Eq. 6 with the causal rule and the forced blocks (Section 4.1, Stage 1).
-    J holds the scores of the visible blocks 0 .. b_t.  Block 0 (first) and block b_t (the one
-    containing the query) are always kept and count inside the budget m."""
+    J holds the scores of the visible blocks b0 .. b_t.  Block b0 (first) and block b_t (the one
+    containing the query) are always kept and count inside the budget m.  Returns block ids."""
     n_vis = J.size
-    b_t = n_vis - 1
     if n_vis <= m:
-        return np.arange(n_vis, dtype=np.int64)
+        return b0 + np.arange(n_vis, dtype=np.int64)
     assert m >= 2, "m >= 2 is needed to hold the two forced blocks"
-    inner = np.arange(1, b_t, dtype=np.int64)
-    kept = top_select(J[1:b_t], inner, m - 2)
-    return np.sort(np.concatenate([[0], kept, [b_t]]).astype(np.int64))
+    last = n_vis - 1
+    inner = np.arange(1, last, dtype=np.int64)
+    kept = top_select(J[1:last], inner, m - 2)
+    return b0 + np.sort(np.concatenate([[0], kept, [last]]).astype(np.int64))
 
 
 def hisa_block_score_topk(*, q, q_dtype, w, q_seq, q_pos, pooled, pooled_dtype, B, m,
-                          queries=None):
-    """Stage 1 for the listed queries.  pooled: stored bits [n_seq, M, d].
+                          queries=None, q_lo=None):
+    """Stage 1 for the listed queries.  pooled: stored bits [n_seq, M, d].  q_lo: first visible
+    position per query (None: 0).
     Returns (block_idx [n, m] int32 ascending then -1, J [n, M] float64 with -inf for invisible
     blocks)."""
     T = q.shape[0]
@@ -160,24 +167,28 @@ def hisa_block_score_topk(*, q, q_dtype, w, q_seq, q_pos, pooled, pooled_dtype, 
     for i, t in enumerate(queries):
         n = 0 if q_seq is None else int(q_seq[t])
         b_t = int(q_pos[t]) // B
+        b_0 = 0 if q_lo is None else int(q_lo[t]) // B
+        if b_t < b_0:
+            continue                          # the query sees no key
         qt = decode(q[t], q_dtype)
-        pk = decode(pooled[n, :b_t + 1], pooled_dtype)
+        pk = decode(pooled[n, b_0:b_t + 1], pooled_dtype)
         J = score(qt, w[t].astype(np.float64), pk)
-        Jout[i, :b_t + 1] = J
-        C = select_blocks(J, m)
+        Jout[i, b_0:b_t + 1] = J
+        C = select_blocks(J, m, b_0)
         block_idx[i, :C.size] = C
     return block_idx, Jout
 
 
 # ----------------------------------------------------------------------------- Stage 2
-def candidate_tokens(C: np.ndarray, pos: int, B: int) -> np.ndarray:
-    """Eq. 7 with the causal mask: tokens of the kept blocks that the query can see, ascending."""
+def candidate_tokens(C: np.ndarray, pos: int, B: int, lo: int = 0) -> np.ndarray:
+    """Eq. 7 with the causal mask: tokens of the kept blocks that the query can see
+    (lo <= s <= pos), ascending."""
     toks = (C[:, None] * B + np.arange(B, dtype=np.int64)[None, :]).reshape(-1)
-    return toks[toks <= pos]
+    return toks[(toks <= pos) & (toks >= lo)]
 
 
 def hisa_token_refine_topk(*, q, q_dtype, w, q_seq, q_pos, keys, k_dtype, k_scale, B, m,
-                           block_idx, k, queries=None):
+                           block_idx, k, queries=None, q_lo=None):
     """Stage 2 (Eqs. 8-9) for the listed queries; block_idx [n, m] is aligned with `queries`.
     Returns (topk_idx [n, k] int32 ascending then -1, topk_scores [n, k] float64 (nan padding),
     cand_scores [n, m*B] float64, slot c = (kept block c//B, offset c%B), -inf where masked)."""
@@ -189,12 +200,15 @@ def hisa_token_refine_topk(*, q, q_dtype, w, q_seq, q_pos, keys, k_dtype, k_scal
     for i, t in enumerate(queries):
         n = 0 if q_seq is None else int(q_seq[t])
         pos = int(q_pos[t])
+        lo = 0 if q_lo is None else int(q_lo[t])
         C = block_idx[i][block_idx[i] >= 0].astype(np.int64)
-        toks = candidate_tokens(C, pos, B)
+        toks = candidate_tokens(C, pos, B, lo)
         sc = None if k_scale is None else k_scale[n, toks]
         kc = decode(keys[n, toks], k_dtype, sc)
         I = score(decode(q[t], q_dtype), w[t].astype(np.float64), kc)
-        cand_scores[i, :toks.size] = I       # kept blocks ascending => visible slots are a prefix
+        if toks.size:                         # slot of token s: its kept block's rank * B + s % B
+            rank = np.searchsorted(C, toks // B)
+            cand_scores[i, rank * B + toks % B] = I
         sel = top_select(I, toks, k)
         topk_idx[i, :sel.size] = sel
         lookup = dict(zip(toks.tolist(), I.tolist()))
@@ -203,26 +217,27 @@ def hisa_token_refine_topk(*, q, q_dtype, w, q_seq, q_pos, keys, k_dtype, k_scal
 
 
 def hisa_indexer(*, q, q_dtype, w, q_seq, q_pos, keys, k_dtype, k_scale, seq_len, B, m, k,
-                 pooled_dtype, queries=None, pooled=None):
+                 pooled_dtype, queries=None, pooled=None, q_lo=None):
     """Algorithm 1 end to end for the listed queries.  Returns dict with pooled, block_idx, J,
     topk_idx, topk_scores, cand_scores."""
     if pooled is None:
         pooled = pool_blocks(keys, k_dtype, k_scale, seq_len, B, pooled_dtype)
     block_idx, J = hisa_block_score_topk(q=q, q_dtype=q_dtype, w=w, q_seq=q_seq, q_pos=q_pos,
                                          pooled=pooled, pooled_dtype=pooled_dtype, B=B, m=m,
-                                         queries=queries)
+                                         queries=queries, q_lo=q_lo)
     topk_idx, topk_scores, cand = hisa_token_refine_topk(
         q=q, q_dtype=q_dtype, w=w, q_seq=q_seq, q_pos=q_pos, keys=keys, k_dtype=k_dtype,
-        k_scale=k_scale, B=B, m=m, block_idx=block_idx, k=k, queries=queries)
+        k_scale=k_scale, B=B, m=m, block_idx=block_idx, k=k, queries=queries, q_lo=q_lo)
     return dict(pooled=pooled, block_idx=block_idx, J=J, topk_idx=topk_idx,
                 topk_scores=topk_scores, cand_scores=cand)
 
 
 # ----------------------------------------------------------------------------- flat DSA (Eqs. 1-2)
 def dsa_flat_indexer_topk(*, q, q_dtype, w, q_seq, q_pos, keys, k_dtype, k_scale, k,
-                          queries=None, return_scores=False, chunk=16384):
-    """Eqs. 1-2 over the whole causal prefix s <= pos_t.  Returns (topk_idx [n, k] int32 ascending
-    then -1, topk_scores [n, k] float64) and, if asked, the list of full score rows."""
+                          queries=None, return_scores=False, chunk=16384, q_lo=None):
+    """Eqs. 1-2 over the whole causal prefix lo_t <= s <= pos_t (lo_t = 0 unless q_lo is given).
+    Returns (topk_idx [n, k] int32 ascending then -1, topk_scores [n, k] float64) and, if asked,
+    the list of full score rows (row i covers the positions lo_t .. pos_t)."""
     T = q.shape[0]
     queries = np.arange(T) if queries is None else np.asarray(queries)
     topk_idx = np.full((queries.size, k), -1, dtype=np.int32)
@@ -233,14 +248,15 @@ def dsa_flat_indexer_topk(*, q, q_dtype, w, q_seq, q_pos, keys, k_dtype, k_scale
         pos = int(q_pos[t])
         qt = decode(q[t], q_dtype)
         wt = w[t].astype(np.float64)
-        I = np.empty(pos + 1, dtype=np.float64)
-        for lo in range(0, pos + 1, chunk):   # chunked only to bound the float64 copy of the keys
+        first = 0 if q_lo is None else int(q_lo[t])
+        I = np.empty(max(pos + 1 - first, 0), dtype=np.float64)
+        for lo in range(first, pos + 1, chunk):   # chunked only to bound the float64 copy of the keys
             hi = min(lo + chunk, pos + 1)
             sc = None if k_scale is None else k_scale[n, lo:hi]
-            I[lo:hi] = score(qt, wt, decode(keys[n, lo:hi], k_dtype, sc))
-        sel = top_select(I, np.arange(pos + 1, dtype=np.int64), k)
+            I[lo - first:hi - first] = score(qt, wt, decode(keys[n, lo:hi], k_dtype, sc))
+        sel = top_select(I, np.arange(first, pos + 1, dtype=np.int64), k)
         topk_idx[i, :sel.size] = sel
-        topk_scores[i, :sel.size] = I[sel]
+        topk_scores[i, :sel.size] = I[sel - first]
         if return_scores:
             rows.append(I)
     if return_scores:

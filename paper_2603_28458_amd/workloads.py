@@ -105,6 +105,7 @@ class Workload:
     q_seq: Optional[np.ndarray] = field(repr=False, default=None)    # [T] int32 or None (all 0)
     q_pos: Optional[np.ndarray] = field(repr=False, default=None)    # [T] int32 or None
     q_pos0: int = 0                                                  # q_pos[t] = q_pos0 + t if q_pos is None
+    q_lo: Optional[np.ndarray] = field(repr=False, default=None)     # [T] int32 first visible position, or None (0)
     needles: list = field(default_factory=list)                      # (seq, p, t_star, j_star)
     seed: int = 0
 
@@ -219,6 +220,30 @@ def make_workload(name: str, *, n_seq: int = 1, seq_len, T: int, H: int, d: int,
                     q_dtype=q_dtype, k_dtype=k_dtype, pooled_dtype=pooled_dtype, keys=keys,
                     k_scale=k_scale, seq_len=seq_len.astype(np.int32), q=q_bits, w=w, q_seq=q_seq,
                     q_pos=q_pos, q_pos0=q_pos0, needles=needles, seed=seed)
+
+
+def pack(wl: Workload, name: Optional[str] = None) -> Workload:
+    """The sequences of a "varlen" workload laid end to end in ONE key stream, without padding
+    between them (Section 4.1: blocks of the packed stream may straddle two sequences).  Query t
+    keeps its data; its position becomes start(sequence) + position and it carries that start as
+    its first visible position.  Pure data movement: same stored bits, new coordinates."""
+    assert wl.q_seq is not None and wl.q_pos is not None and wl.q_lo is None
+    lens = wl.seq_len.astype(np.int64)
+    starts = np.concatenate([[0], np.cumsum(lens)[:-1]])
+    total = int(lens.sum())
+    s_max = int(-(-total // wl.B) * wl.B)
+    keys = np.zeros((1, s_max) + wl.keys.shape[2:], dtype=wl.keys.dtype)
+    k_scale = None if wl.k_scale is None else np.ones((1, s_max), dtype=np.float32)
+    for n in range(wl.n_seq):
+        keys[0, starts[n]:starts[n] + lens[n]] = wl.keys[n, :lens[n]]
+        if k_scale is not None:
+            k_scale[0, starts[n]:starts[n] + lens[n]] = wl.k_scale[n, :lens[n]]
+    seqs = wl.q_seq.astype(np.int64)
+    return Workload(name=name or wl.name + "_packed", n_seq=1, s_max=s_max, T=wl.T, H=wl.H, d=wl.d, B=wl.B,
+                    m=wl.m, k=wl.k, q_dtype=wl.q_dtype, k_dtype=wl.k_dtype, pooled_dtype=wl.pooled_dtype,
+                    keys=keys, k_scale=k_scale, seq_len=np.array([total], dtype=np.int32), q=wl.q, w=wl.w,
+                    q_seq=None, q_pos=(starts[seqs] + wl.q_pos).astype(np.int32), q_pos0=0,
+                    q_lo=starts[seqs].astype(np.int32), needles=[], seed=wl.seed)
 
 
 # The five benchmark configurations (shapes: Section 5.1 of the paper for B, m, k; H and d are

@@ -340,6 +340,94 @@ def test_decode_layout_and_subset_of_queries():
     assert np.array_equal(sub["topk_idx"][1], r["topk_idx"][0])
 
 
+# ------------------------------------------------------------------ packed sequences (first visible position)
+def _varlen(lens, seed=31, **kw):
+    p = dict(n_seq=len(lens), seq_len=lens, T=int(sum(lens)), H=3, d=8, B=8, m=4, k=10, q_dtype="f32",
+             k_dtype="f32", mode="varlen", seed=seed)
+    p.update(kw)
+    return W.make_workload("v", **p)
+
+
+def test_packed_sequences_on_block_boundaries_equal_the_padded_layout():
+    # every sequence a multiple of B long: the packed stream's blocks are the sequences' own blocks,
+    # so each query must keep the same blocks and tokens, shifted by its sequence's start
+    wl = _varlen([40, 16, 64, 8])
+    pk = W.pack(wl)
+    a, b = oracle_hisa(wl), oracle_hisa(pk)
+    fa, _ = oracle_flat(wl)
+    fb, _ = oracle_flat(pk)
+    lo = pk.q_lo.astype(np.int64)
+    for t in range(wl.T):
+        for x, y, unit in ((a["block_idx"][t], b["block_idx"][t], wl.B), (a["topk_idx"][t], b["topk_idx"][t], 1),
+                           (fa[t], fb[t], 1)):
+            assert np.array_equal(np.where(x >= 0, x + lo[t] // unit, -1), y), t
+    np.testing.assert_array_equal(a["topk_scores"], b["topk_scores"])
+
+
+def test_zero_first_position_is_the_plain_indexer():
+    wl = _small()
+    r0 = oracle_hisa(wl)
+    wl.q_lo = np.zeros(wl.T, dtype=np.int32)
+    r1 = oracle_hisa(wl)
+    for key in ("block_idx", "topk_idx", "J", "cand_scores"):
+        np.testing.assert_array_equal(r0[key], r1[key])
+
+
+def _brute_force_packed(pk, t):
+    """Section 4.1 on a packed stream with Python floats, loops and sorted(): blocks of the stream,
+    pooled over everything they hold, visible blocks lo // B .. pos // B with both ends forced,
+    tokens lo .. pos of the kept blocks."""
+    K = pk.keys[0].astype(float).tolist()
+    Q = pk.q[t].astype(float).tolist()
+    Wt = pk.w[t].astype(float).tolist()
+    pos, lo = int(pk.q_pos[t]), int(pk.q_lo[t])
+    B, d, H, m, k = pk.B, pk.d, pk.H, pk.m, pk.k
+    L = int(pk.seq_len[0])
+
+    def sc(vec):
+        tot = 0.0
+        for j in range(H):
+            dot = sum(Q[j][i] * vec[i] for i in range(d))
+            if dot > 0:
+                tot += Wt[j] * dot
+        return tot
+
+    b0, b1 = lo // B, pos // B
+    pooled = {}
+    for b in range(b0, b1 + 1):
+        toks = range(b * B, min((b + 1) * B, L))
+        pooled[b] = [float(np.float32(sum(K[s][i] for s in toks) / len(toks))) for i in range(d)]
+    if b1 - b0 + 1 <= m:
+        C = list(range(b0, b1 + 1))
+    else:
+        inner = sorted(range(b0 + 1, b1), key=lambda b: (-sc(pooled[b]), b))[:m - 2]
+        C = sorted([b0, b1] + inner)
+    cand = [s for b in C for s in range(b * B, (b + 1) * B) if lo <= s <= pos]
+    hisa = sorted(sorted(cand, key=lambda s: (-sc(K[s]), s))[:k])
+    flat = sorted(sorted(range(lo, pos + 1), key=lambda s: (-sc(K[s]), s))[:k])
+    return C, hisa, flat
+
+
+def test_packed_sequences_with_straddling_blocks_brute_force_and_invariants():
+    wl = _varlen([37, 5, 61, 19, 3], seed=32)           # starts 0, 37, 42, 103, 122: blocks straddle
+    pk = W.pack(wl)
+    r = oracle_hisa(pk)
+    f, _ = oracle_flat(pk)
+    lo, pos = pk.q_lo.astype(np.int64), pk.q_pos.astype(np.int64)
+    assert np.any(lo % pk.B != 0)
+    for t in range(pk.T):
+        C, hisa, flat = _brute_force_packed(pk, t)
+        bi = r["block_idx"][t][r["block_idx"][t] >= 0]
+        ti = r["topk_idx"][t][r["topk_idx"][t] >= 0]
+        assert bi.tolist() == C and ti.tolist() == hisa and f[t][f[t] >= 0].tolist() == flat, t
+        # the first and the last visible block are kept, the budget holds, nothing outside [lo, pos]
+        n_vis = pos[t] // pk.B - lo[t] // pk.B + 1
+        assert bi[0] == lo[t] // pk.B and bi[-1] == pos[t] // pk.B and bi.size == min(pk.m, n_vis)
+        assert ti.min() >= lo[t] and ti.max() <= pos[t] and ti.size == min(pk.k, pos[t] - lo[t] + 1)
+        if n_vis <= pk.m:                                # every visible block kept: HISA = flat
+            assert ti.tolist() == flat, t
+
+
 def test_iou_definition():
     assert O.iou(np.array([1, 2, 3, -1]), np.array([2, 3, 4, 5])) == 2 / 5
     assert O.iou(np.array([1, 2]), np.array([2, 1])) == 1.0

@@ -9,7 +9,7 @@ RTOL = {"f32": 1e-5, "bf16": 2e-2, "fp8_e4m3": 2e-2}
 
 
 def oracle_args(wl, *, keys=True):
-    a = dict(q=wl.q, q_dtype=wl.q_dtype, w=wl.w, q_seq=wl.q_seq, q_pos=wl.positions())
+    a = dict(q=wl.q, q_dtype=wl.q_dtype, w=wl.w, q_seq=wl.q_seq, q_pos=wl.positions(), q_lo=wl.q_lo)
     if keys:
         a.update(keys=wl.keys, k_dtype=wl.k_dtype, k_scale=wl.k_scale)
     return a
