@@ -77,6 +77,13 @@ typedef struct {
   const float*   w;         /* [T, H] fp32 gates, any sign (device)                              */
   const int32_t* q_seq;     /* [T] sequence id of each query, or NULL: all queries in sequence 0 */
   const int32_t* q_pos;     /* [T] position of each query, or NULL: q_pos[t] = q_pos0 + t        */
+  const int32_t* q_lo;      /* [T] first visible position of each query, or NULL: 0.  For sequences
+                               packed into one key stream without padding (Section 4.1: a block may
+                               then straddle two sequences): q_lo[t] = first token of the query's
+                               sequence in the stream, q_pos[t] its own position there; the query
+                               sees the keys q_lo[t] .. q_pos[t].  Blocks stay multiples of B of the
+                               stream and are pooled over everything they hold; the visible blocks
+                               are q_lo/B .. q_pos/B, the first and the last of them forced.  (device) */
   int32_t        T;
   int32_t        H;
   int32_t        q_pos0;

@@ -65,6 +65,7 @@ ScoreArgs base_args(const hisa_queries* q, const hisa_keys* k) {
   a.w = q->w;
   a.q_seq = q->q_seq;
   a.q_pos = q->q_pos;
+  a.q_lo = q->q_lo;
   a.q_pos0 = q->q_pos0;
   a.H = q->H;
   a.d = k->d;
@@ -168,6 +169,7 @@ SelectArgs select_base(const hisa_queries* q, const hisa_keys* k) {
   SelectArgs s{};
   s.q_seq = q->q_seq;
   s.q_pos = q->q_pos;
+  s.q_lo = q->q_lo;
   s.seq_len = k->seq_len;
   s.q_pos0 = q->q_pos0;
   s.n_seq = k->n_seq;
@@ -358,6 +360,7 @@ int hisa_block_sparse_tokens(const hisa_queries* queries, const hisa_keys* keys,
   ScoreArgs a{};
   a.q_seq = queries->q_seq;
   a.q_pos = queries->q_pos;
+  a.q_lo = queries->q_lo;
   a.q_pos0 = queries->q_pos0;
   a.seq_len = keys->seq_len;
   a.n_seq = keys->n_seq;
@@ -448,7 +451,7 @@ int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, co
     hipLaunchKernelGGL(k_fill_f32, dim3((unsigned)((n + 255) / 256 > 4096 ? 4096 : (n + 255) / 256)),
                        dim3(256), 0, s, J, n, -__builtin_inff());
   }
-  launch_score(path, pooled_dtype, a, M, !queries->q_seq && !queries->q_pos, s);
+  launch_score(path, pooled_dtype, a, M, !queries->q_seq && !queries->q_pos && !queries->q_lo, s);
 
   SelectArgs sa = select_base(queries, keys);
   sa.scores = J;
@@ -586,7 +589,7 @@ int dsa_flat_indexer_topk(const hisa_queries* queries, const hisa_keys* keys, in
   float* scores = (float*)ws;
   float* part_sc = (float*)((char*)ws + chunk * p.ld * 4);
   int32_t* part_id = (int32_t*)((char*)part_sc + chunk * (long)p.n_seg * k * 4);
-  const bool consecutive = !queries->q_seq && !queries->q_pos;
+  const bool consecutive = !queries->q_seq && !queries->q_pos && !queries->q_lo;
 
   for (long t0 = 0; t0 < T; t0 += chunk) {
     const int tc = (int)((T - t0) < chunk ? (T - t0) : chunk);

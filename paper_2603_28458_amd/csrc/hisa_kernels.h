@@ -36,6 +36,7 @@ struct ScoreArgs {
   const float* w;            // [T, H]
   const int32_t* q_seq;      // [T] or null
   const int32_t* q_pos;      // [T] or null
+  const int32_t* q_lo;       // [T] first visible position (packed sequences) or null: 0
   int q_pos0;
   int H, d;
   const void* keys;          // [n_seq, rows_per_seq, d]: token keys, or pooled keys (pos_div = B)
@@ -68,6 +69,15 @@ __device__ __forceinline__ int query_pos(const ScoreArgs& a, int t, int& seq) {
 
 __device__ __forceinline__ int visible_rows(const ScoreArgs& a, int pos) {
   return pos < 0 ? 0 : pos / a.pos_div + 1;
+}
+
+// First visible position of query t: its sequence's first token when sequences are packed into one
+// key stream (Section 4.1: blocks may then straddle two sequences), else 0.  The query sees the
+// positions lo .. pos; lo == pos + 1 means it sees nothing.
+__device__ __forceinline__ int query_lo(const int32_t* q_lo, int t, int pos) {
+  int lo = q_lo ? q_lo[t] : 0;
+  lo = lo < 0 ? 0 : lo;
+  return lo > pos + 1 ? pos + 1 : lo;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -187,13 +197,14 @@ __global__ __launch_bounds__(256) void k_block_sparse_tokens(ScoreArgs a, int32_
   const int t = blockIdx.y;
   int seq;
   const int pos = query_pos(a, t, seq);
+  const int lo = query_lo(a.q_lo, t, pos);
   const int n_slots = a.m * a.B;
   const int n_blocks = (int)(a.rows_per_seq / a.B);
   for (int c = blockIdx.x * 256 + threadIdx.x; c < n_slots; c += gridDim.x * 256) {
     const int slot = c / a.B;
     const int blk = a.block_idx[(long)t * a.m + slot];
     const int tok = blk * a.B + (c - slot * a.B);
-    tokens[(long)t * n_slots + c] = (blk >= 0 && blk < n_blocks && tok <= pos) ? tok : -1;
+    tokens[(long)t * n_slots + c] = (blk >= 0 && blk < n_blocks && tok <= pos && tok >= lo) ? tok : -1;
   }
 }
 
@@ -301,18 +312,20 @@ __global__ __launch_bounds__(256) void k_score_ranges_f32(ScoreArgs a, int keys_
   __syncthreads();
   const bool gather = a.block_idx != nullptr;
   const int n_total = gather ? a.m * a.B : visible_rows(a, pos);
+  const int lo = query_lo(a.q_lo, t, pos);
+  const int lo_row = lo / a.pos_div;   // first visible row when the rows are blocks or tokens in order
   const int c0 = blockIdx.x * keys_per_wg;
   const int c1 = (c0 + keys_per_wg) < n_total ? (c0 + keys_per_wg) : n_total;
   const float* kbase = (const float*)a.keys + (long)seq * a.rows_per_seq * d;
   float* out = a.out + (long)blockIdx.y * a.ld;
   for (int c = c0 + tid; c < c1; c += 256) {
     long row = c;
-    bool valid = true;
+    bool valid = c >= lo_row;
     if (gather) {
       const int slot = c / a.B, off = c - slot * a.B;
       const int blk = a.block_idx[(long)t * a.m + slot];
       row = (long)blk * a.B + off;
-      valid = blk >= 0 && row <= pos;
+      valid = blk >= 0 && row <= pos && row >= lo;
     }
     float s = neg_inf();
     if (valid) {
@@ -491,8 +504,13 @@ __global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
   const bool gather = a.block_idx != nullptr;
   const int n_vis = gather ? pos + 1 : visible_rows(a, pos);
   const int n_tiles = gather ? a.m * (a.B >> 5) : (n_vis + 31) >> 5;
+  // first visible row: a token when gathering, else a row of the array in order (token or block)
+  const int lo_row = gather ? query_lo(a.q_lo, t, pos) : query_lo(a.q_lo, t, pos) / a.pos_div;
   const int v0 = blockIdx.x * 4 * a.tiles_per_wave;
   if (v0 >= n_tiles) return;
+  // in-order rows below the first visible one are neither scored nor written: the select starts
+  // at the first visible row (rounded down to four)
+  if (!gather && (v0 + 4 * a.tiles_per_wave) * 32 <= lo_row) return;
   float* out = a.out + (long)blockIdx.y * a.ld;
   const int n_blocks = (int)(a.rows_per_seq / a.B);
 
@@ -507,7 +525,8 @@ __global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
     if (lane < a.tiles_per_wave && v < n_tiles) {
       const TileLoc Lc = tile_loc(a, t, v, gather);
       my_out = (int)Lc.out0;
-      const bool ok = Lc.row0 >= 0 && Lc.row0 < n_vis && (!gather || Lc.row0 / a.B < n_blocks);
+      const bool ok = Lc.row0 >= 0 && Lc.row0 < n_vis && Lc.row0 + 32 > lo_row &&
+                      (!gather || Lc.row0 / a.B < n_blocks);
       if (ok) my_row = (int)Lc.row0;
       else if (gather)
         for (int x = 0; x < 32; ++x) out[my_out + x] = neg_inf();
@@ -541,7 +560,7 @@ __global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
   auto row_at = [&](int j) { return rows.at(j); };
   auto finish = [&](int j, float s) {
     const int row = rows.at(j) + (lane & 31);
-    if (row >= n_vis) s = neg_inf();
+    if (row >= n_vis || row < lo_row) s = neg_inf();
     if (lane < 32 && (gather || row < n_vis)) out[outs.at(j) + lane] = s;
   };
   wave_pipeline<HG, KDT, NB>(fo, krsrc, srsrc, ring_addr, nj, row_at, finish);
@@ -725,6 +744,7 @@ struct SelectArgs {
   const int32_t* idx_in;     // MAP_PAIRS: [rows, ld] ids aligned with scores
   const int32_t* q_seq;      // position info of the queries (FLAT / BLOCKS)
   const int32_t* q_pos;
+  const int32_t* q_lo;       // first visible position per query or null (FLAT / BLOCKS)
   const int32_t* seq_len;
   int q_pos0, n_seq, pos_div;
   int t_begin;               // global query index of row 0
@@ -750,6 +770,7 @@ __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
   const float* sc = a.scores + (long)row * a.ld;
   int n = a.n_fixed;
   int base = 0;
+  int first_vis = 0;   // MAP_BLOCKS: entry of the first visible block (0 unless sequences are packed)
   if (MAP == MAP_FLAT || MAP == MAP_BLOCKS) {
     int s = a.q_seq ? a.q_seq[t] : 0;
     s = s < 0 ? 0 : (s >= a.n_seq ? a.n_seq - 1 : s);
@@ -758,9 +779,15 @@ __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
     pos = pos < sl ? pos : sl - 1;
     int n_vis = pos < 0 ? 0 : pos / a.pos_div + 1;
     n_vis = n_vis < a.ld ? n_vis : (int)a.ld;   // never past the score row, whatever seq_len says
+    // this segment's rows, cut at the first visible one rounded down to four (16-byte loads; the
+    // up to three rows in between were written as -inf by the scoring kernel)
+    const int lo_row = query_lo(a.q_lo, t, pos) / a.pos_div;
+    const int seg_end = (seg + 1) * a.seg_len < n_vis ? (seg + 1) * a.seg_len : n_vis;
     base = seg * a.seg_len;
-    n = n_vis - base;
-    n = n < 0 ? 0 : (n > a.seg_len ? a.seg_len : n);
+    base = base > (lo_row & ~3) ? base : (lo_row & ~3);
+    n = seg_end - base;
+    n = (n < 0 || lo_row >= n_vis) ? 0 : n;     // (first visible row past the last: the query sees nothing)
+    first_vis = lo_row - base;                  // < 0 in later segments: no forced entry there
   }
   const long orow = (long)row * a.n_seg + seg;
   int32_t* oi = a.out_idx + orow * a.k;
@@ -770,7 +797,7 @@ __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
   // the row through a buffer descriptor of exactly n floats: no branch at the ragged end
   const __amdgpu_buffer_rsrc_t rrow = key_buffer(rowp, (long)n * 4);
   auto key_of = [&](int i, float v) -> uint32_t {
-    if (MAP == MAP_BLOCKS && (i == 0 || i == n_last)) return 0xffffffffu;   // forced blocks
+    if (MAP == MAP_BLOCKS && (i == first_vis || i == n_last)) return 0xffffffffu;   // forced blocks
     return ordered_key(v);
   };
   auto load4 = [&](int q) -> uint4 {
@@ -862,8 +889,12 @@ __global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(Sel
   pos = pos < sl ? pos : sl - 1;
   int n = pos < 0 ? 0 : pos + 1;
   n = n < a.ld ? n : (int)a.ld;   // never past the score row, whatever seq_len says
+  // packed sequences: the row starts at the first visible position rounded down to four (16-byte
+  // loads; the up to three entries in between hold -inf); ids are row-relative until the output
+  const int id0 = query_lo(a.q_lo, t, pos) & ~3;
+  n = n > id0 ? n - id0 : 0;
   const int k = a.k;
-  const float* rowp = a.scores + (long)row * a.ld;
+  const float* rowp = a.scores + (long)row * a.ld + id0;
   int32_t* oi = a.out_idx + (long)row * k;
   float* os = a.out_scores ? a.out_scores + (long)row * k : nullptr;
 
@@ -879,7 +910,7 @@ __global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(Sel
     for (int p = tid; p < n; p += THREADS) bad |= rowp[p] == neg_inf();
     if (!__syncthreads_or(bad)) {
       for (int p = tid; p < k; p += THREADS) {
-        oi[p] = p < n ? p : -1;
+        oi[p] = p < n ? id0 + p : -1;
         if (os) os[p] = p < n ? rowp[p] : neg_inf();
       }
       return;
@@ -1145,13 +1176,13 @@ __global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(Sel
   for (int j = tid; j < n_s; j += THREADS) {
     const int x = sure_idx[j];
     const int p = j + lower_bound(win_idx, n_w, x);
-    oi[p] = x;
+    oi[p] = id0 + x;
     if (os) os[p] = key_to_score(sure_key[j]);
   }
   for (int j = tid; j < n_w; j += THREADS) {
     const int y = win_idx[j];
     const int p = j + lower_bound(sure_idx, n_s, y);
-    oi[p] = y;
+    oi[p] = id0 + y;
     if (os) os[p] = key_to_score(win_key[j]);
   }
   for (int p = n_s + n_w + tid; p < k; p += THREADS) {
@@ -1162,19 +1193,20 @@ __global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(Sel
 
 // ------------------------------------------------------------------------------------------
 // Stage 1 (Eqs. 5-6) of ONE query inside a workgroup of NW waves that already holds the query
-// fragment: the pooled keys (bf16, [n_seq, n_blocks, d]) of the visible blocks 0 .. b_t go through
+// fragment: the pooled keys (bf16, [n_seq, n_blocks, d]) of the blocks 0 .. b_t go through
 // the scoring pipeline in tiles of 32 (wave w takes tiles w, w + NW, ...), the block scores land
-// in sc[0 .. 32 * tiles) (-inf past b_t), select_topk keeps a.m of them with the first and the
-// query's own block forced (E1 blocks per thread: NW * 64 * E1 >= n_blocks), and the kept ids go
+// in sc[0 .. 32 * tiles) (-inf past b_t and below the first visible block lo / B), select_topk keeps
+// a.m of them with the first visible and the query's own block forced (E1 blocks per thread: NW * 64 * E1 >= n_blocks), and the kept ids go
 // to blk_lds[0 .. a.m) ascending, -1 padded.  smem: the NW * NB tile rings of TILE bytes (reused
 // by the select).  Ends with a barrier: ids visible, score area and rings free again.
 template <int HG, int NW, int NB, int E1, int TILE>
 __device__ __forceinline__ void stage1_in_workgroup(const QFrag<HG>& f, const ScoreArgs& a, const void* pooled,
-                                                    int seq, int pos, int n_blocks, unsigned char* smem,
+                                                    int seq, int pos, int lo, int n_blocks, unsigned char* smem,
                                                     float* sc, int32_t* blk_lds, int wave) {
   constexpr int NT = NW * 64;
   const int lane = threadIdx.x & 63;
   const int n_bvis = pos < 0 ? 0 : pos / a.B + 1;
+  const int b_first = lo / a.B;   // first visible block (0 unless sequences are packed)
   const int nt1 = (n_bvis + 31) >> 5;
   const int nj1 = nt1 > wave ? (nt1 - wave + NW - 1) / NW : 0;
   const __amdgpu_buffer_rsrc_t prsrc =
@@ -1184,14 +1216,14 @@ __device__ __forceinline__ void stage1_in_workgroup(const QFrag<HG>& f, const Sc
       [&](int j) { return (wave + NW * j) * 32; },
       [&](int j, float s) {
         const int b = (wave + NW * j) * 32 + (lane & 31);
-        if (lane < 32) sc[b] = b < n_bvis ? s : neg_inf();
+        if (lane < 32) sc[b] = (b < n_bvis && b >= b_first) ? s : neg_inf();
       });
   __syncthreads();   // block scores complete, rings dead
   {
     SelectSmem<NT, E1>& sm1 = *reinterpret_cast<SelectSmem<NT, E1>*>(smem);
     const int n_last = n_bvis - 1;
     auto key_of = [&](int i, float v) -> uint32_t {
-      return (i == 0 || i == n_last) ? 0xffffffffu : ordered_key(v);   // first and own block forced
+      return (i == b_first || i == n_last) ? 0xffffffffu : ordered_key(v);   // first and own block forced
     };
     auto load4 = [&](int q) -> uint4 {
       const float4 v = *reinterpret_cast<const float4*>(sc + 4 * q);
@@ -1200,7 +1232,8 @@ __device__ __forceinline__ void stage1_in_workgroup(const QFrag<HG>& f, const Sc
     };
     auto load1 = [&](int i) -> uint32_t { return key_of(i, sc[i]); };
     auto emit = [&](int p, int i, uint32_t) { blk_lds[p] = i; };
-    const int n_kept = select_topk<NT, E1>(sm1, n_bvis, a.m, load4, load1, emit);
+    // (a first visible block past the query's own: the query sees nothing, nothing is forced)
+    const int n_kept = select_topk<NT, E1>(sm1, b_first <= n_last ? n_bvis : 0, a.m, load4, load1, emit);
     for (int p = n_kept + threadIdx.x; p < a.m; p += NT) blk_lds[p] = -1;
   }
   __syncthreads();
@@ -1238,6 +1271,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
   int seq;
   const int pos = query_pos(a, t, seq);
   const int n_vis = pos + 1;
+  const int lo = query_lo(a.q_lo, t, pos);   // first visible token (0 unless sequences are packed)
 
   // fp8 keys without Stage 1 in this launch: no wave needs the bf16 fragment, and the two-term
   // e4m3 fragment is built once for the workgroup (below) instead of once per wave
@@ -1257,7 +1291,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
     int32_t* blk_lds = reinterpret_cast<int32_t*>(sc + sc_floats);
     blk_ids = blk_lds;
     qfrag_ready<HG>(f);
-    stage1_in_workgroup<HG, NW, NB, E1, kTileBytes>(f, a, pooled, seq, pos, n_blocks, smem, sc, blk_lds, wave);
+    stage1_in_workgroup<HG, NW, NB, E1, kTileBytes>(f, a, pooled, seq, pos, lo, n_blocks, smem, sc, blk_lds, wave);
     if (block_idx_out)
       for (int p = threadIdx.x; p < a.m; p += NT) block_idx_out[(long)t * a.m + p] = blk_lds[p];
   }
@@ -1297,7 +1331,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
   auto finish = [&](int j, float s) {
     const int r = rows.at(j);
     const int row = (r < 0 ? 0 : r) + (lane & 31);
-    if (row >= (r < 0 ? 0 : n_vis)) s = neg_inf();
+    if (row >= (r < 0 ? 0 : n_vis) || row < lo) s = neg_inf();
     if (lane < 32) sc[score_slot((wave + NW * j) * 32 + lane)] = s;
   };
   const uint32_t ring_addr = lds_address(smem) + wave * NB * kTileBytes;

@@ -36,7 +36,8 @@ class _Keys(C.Structure):
 
 class _Queries(C.Structure):
     _fields_ = [("q", C.c_void_p), ("w", C.c_void_p), ("q_seq", C.c_void_p), ("q_pos", C.c_void_p),
-                ("T", C.c_int32), ("H", C.c_int32), ("q_pos0", C.c_int32), ("q_dtype", C.c_int32)]
+                ("q_lo", C.c_void_p), ("T", C.c_int32), ("H", C.c_int32), ("q_pos0", C.c_int32),
+                ("q_dtype", C.c_int32)]
 
 
 _lib = None
@@ -135,13 +136,14 @@ class Keys:
 @dataclass
 class Queries:
     """Indexing queries q [T, H, d] (float32 / bfloat16), gates w [T, H] float32, optional
-    q_seq / q_pos [T] int32; all on the GPU."""
+    q_seq / q_pos / q_lo [T] int32; all on the GPU."""
     q: torch.Tensor
     w: torch.Tensor
     dtype: int
     q_seq: Optional[torch.Tensor] = None
     q_pos: Optional[torch.Tensor] = None
     q_pos0: int = 0
+    q_lo: Optional[torch.Tensor] = None
 
     @property
     def T(self) -> int:
@@ -152,8 +154,8 @@ class Queries:
         return self.q.shape[1]
 
     def c(self) -> _Queries:
-        return _Queries(_ptr(self.q), _ptr(self.w), _ptr(self.q_seq), _ptr(self.q_pos), self.T, self.H,
-                        self.q_pos0, self.dtype)
+        return _Queries(_ptr(self.q), _ptr(self.w), _ptr(self.q_seq), _ptr(self.q_pos), _ptr(self.q_lo),
+                        self.T, self.H, self.q_pos0, self.dtype)
 
 
 def _check(status: int, where: str):
@@ -359,5 +361,5 @@ def to_device(wl, device="cuda:0"):
                 k_scale=dev(wl.k_scale))
     queries = Queries(q=dev(qq, torch.bfloat16 if wl.q_dtype == "bf16" else None), w=dev(wl.w),
                       dtype=DTYPE_CODE[wl.q_dtype], q_seq=dev(wl.q_seq), q_pos=dev(wl.q_pos),
-                      q_pos0=wl.q_pos0)
+                      q_pos0=wl.q_pos0, q_lo=dev(getattr(wl, "q_lo", None)))
     return queries, keys

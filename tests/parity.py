@@ -44,6 +44,19 @@ def sample_queries(wl, n, seed=0):
     return np.array(sorted(pick), dtype=np.int64)
 
 
+def _lo(wl):
+    """First visible position of every query (0 unless the workload packs its sequences)."""
+    return np.zeros(wl.T, dtype=np.int64) if wl.q_lo is None else wl.q_lo.astype(np.int64)
+
+
+def _cand_of(wl, C, pos, lo, cand_row):
+    """The visible candidate tokens of kept blocks C (ascending) and their scores out of a
+    candidate-score row in slot order (slot = rank of the block * B + offset in the block)."""
+    toks = O.candidate_tokens(C, int(pos), wl.B, int(lo))
+    slots = np.searchsorted(C, toks // wl.B) * wl.B + toks % wl.B
+    return toks, cand_row[slots]
+
+
 def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, flat_queries=None):
     """Runs the four entry points on `wl` and checks them on `queries` (all if None).
     Returns a dict of statistics (max relative score error, number of threshold swaps)."""
@@ -125,10 +138,11 @@ def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, 
                             pooled_dtype=wl.pooled_dtype, queries=qs, pooled=want)
     same = [i for i in range(qs.size) if np.array_equal(o_full["block_idx"][i], bi[qs[i]])]
     stats["same_block_sets"] = len(same) / max(1, qs.size)
+    lo = _lo(wl)
     for i in same:
-        toks = O.candidate_tokens(bi[qs[i]][bi[qs[i]] >= 0].astype(np.int64), int(pos[qs[i]]), wl.B)
-        check_set(ti[qs[i]], o_full["topk_idx"][i], toks, o_full["cand_scores"][i, :toks.size], rtol,
-                  f"end-to-end set of query {qs[i]}")
+        toks, sc = _cand_of(wl, bi[qs[i]][bi[qs[i]] >= 0].astype(np.int64), pos[qs[i]], lo[qs[i]],
+                            o_full["cand_scores"][i])
+        check_set(ti[qs[i]], o_full["topk_idx"][i], toks, sc, rtol, f"end-to-end set of query {qs[i]}")
 
     # ---- flat DSA (Eqs. 1-2)
     if check_flat:
@@ -139,10 +153,10 @@ def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, 
         o_fi, o_fs, rows = O.dsa_flat_indexer_topk(**oracle_args(wl), k=wl.k, queries=fq, return_scores=True)
         swaps = 0
         for i, t in enumerate(fq):
-            ids = np.arange(rows[i].size)
+            ids = lo[t] + np.arange(rows[i].size)         # the row covers the positions lo .. pos
             swaps += check_set(fi[t], o_fi[i], ids, rows[i], rtol, f"flat set of query {t}")
             nv = int((fi[t] >= 0).sum())
-            check_scores(fs[t, :nv][None], rows[i][fi[t, :nv]][None], rtol, f"flat scores of query {t}")
+            check_scores(fs[t, :nv][None], rows[i][fi[t, :nv] - lo[t]][None], rtol, f"flat scores of query {t}")
             assert np.all(np.isneginf(fs[t, nv:]))
         stats["flat_swaps"] = swaps
         stats["iou_hisa_flat"] = float(np.mean([O.iou(ti[t], fi[t]) for t in qs]))
@@ -154,6 +168,7 @@ def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, 
 def _check_block_sets(wl, qs, bi, o_bi, o_J, rtol, what):
     """Eq. 6 with the forced blocks: shape rules, then the threshold rule on the free slots."""
     pos = wl.positions()
+    lo = _lo(wl)
     swaps = 0
     for i, t in enumerate(qs):
         row = bi[t]
@@ -161,28 +176,29 @@ def _check_block_sets(wl, qs, bi, o_bi, o_J, rtol, what):
             assert np.all(row == -1), (what, t)
             continue
         b_t = int(pos[t]) // wl.B
+        b_0 = int(lo[t]) // wl.B             # first visible block (0 unless sequences are packed)
         v = row[row >= 0]
-        assert v.size == min(wl.m, b_t + 1), (what, t, v.size)
-        assert v[0] == 0 and v[-1] == b_t, f"{what}: query {t}: forced blocks missing"
+        assert v.size == min(wl.m, b_t - b_0 + 1), (what, t, v.size)
+        assert v[0] == b_0 and v[-1] == b_t, f"{what}: query {t}: forced blocks missing"
         assert np.all(row[v.size:] == -1) and np.all(np.diff(v) > 0)
-        if b_t + 1 > wl.m:
-            # the forced blocks 0 and b_t never take part in a swap: compare the free slots
+        if b_t - b_0 + 1 > wl.m:
+            # the forced blocks never take part in a swap: compare the free slots
             ov = o_bi[i][o_bi[i] >= 0]
-            swaps += check_set(v[1:-1], ov[1:-1], np.arange(1, b_t), o_J[i, 1:b_t], rtol,
+            swaps += check_set(v[1:-1], ov[1:-1], np.arange(b_0 + 1, b_t), o_J[i, b_0 + 1:b_t], rtol,
                                f"{what} block set of query {t}")
         else:
-            assert np.array_equal(v, np.arange(b_t + 1))
+            assert np.array_equal(v, np.arange(b_0, b_t + 1))
             assert np.all(row[v.size:] == -1)
     return swaps
 
 
 def _check_token_sets(wl, qs, bi, ti, ts, o_ti, o_cand, rtol, what):
     pos = wl.positions()
+    lo = _lo(wl)
     swaps = 0
     for i, t in enumerate(qs):
         C = bi[t][bi[t] >= 0].astype(np.int64)
-        toks = O.candidate_tokens(C, int(pos[t]), wl.B)
-        sc = o_cand[i, :toks.size]
+        toks, sc = _cand_of(wl, C, pos[t], lo[t], o_cand[i])
         swaps += check_set(ti[t], o_ti[i], toks, sc, rtol, f"{what} token set of query {t}")
         nv = int((ti[t] >= 0).sum())
         assert nv == min(wl.k, toks.size)

@@ -35,7 +35,7 @@ def test_status_strings_and_version(lib):
 
 
 def _structs(T=512, H=64, d=128, n_seq=1, s_max=1024, qd=hisa.HISA_BF16, kd=hisa.HISA_BF16, fake=0x1000):
-    q = hisa._Queries(fake, fake, None, None, T, H, 0, qd)
+    q = hisa._Queries(fake, fake, None, None, None, T, H, 0, qd)
     k = hisa._Keys(fake, fake, fake, n_seq, s_max, d, kd)
     return q, k
 
@@ -74,7 +74,7 @@ def test_host_side_validation_rejects_before_launch(lib):
     qs, ks = _structs(T=8)
     assert lib.hisa_token_refine_topk(C.byref(qs), C.byref(ks), 128, 8, fake, 512, fake, None, None, None, 0, None) == 5
     # alignment
-    q3 = hisa._Queries(fake + 4, fake, None, None, 512, 64, 0, hisa.HISA_BF16)
+    q3 = hisa._Queries(fake + 4, fake, None, None, None, 512, 64, 0, hisa.HISA_BF16)
     assert lib.dsa_flat_indexer_topk(C.byref(q3), C.byref(k), 64, fake, None, fake, 1 << 30, None) == 6
 
 

@@ -81,6 +81,32 @@ def test_packed_varlen_prefill(k_dtype):
     _run(wl, queries=sample_queries(wl, 200))
 
 
+@pytest.mark.parametrize("k_dtype", ["bf16", "fp8_e4m3"])
+def test_packed_sequences_with_straddling_blocks(k_dtype):
+    # five sequences laid end to end in ONE key stream (Section 4.1: blocks straddle two sequences):
+    # starts 0, 700, 2003, 2260, 2263 against B = 128; every query carries its sequence's start as
+    # first visible position; two-kernel, fused and single-launch paths, and the flat indexer
+    base = W.make_workload(f"pk_{k_dtype}", n_seq=5, seq_len=[700, 1303, 257, 3, 1500], T=3763, H=64, d=128,
+                           B=128, m=4, k=256, q_dtype="bf16", k_dtype=k_dtype, mode="varlen", seed=131)
+    wl = W.pack(base)
+    starts = np.unique(wl.q_lo)
+    edge = [int(np.nonzero(wl.q_pos == p)[0][0]) for s in starts for p in (s, s + 1) if np.any(wl.q_pos == p)]
+    qs = np.unique(np.concatenate([sample_queries(wl, 200), np.array(edge, dtype=np.int64)]))
+    _run(wl, queries=qs)
+
+
+def test_packed_sequences_fp32_and_long_rows():
+    # the fp32 path, and a stream long enough for the streaming top-k of the flat indexer
+    base = W.make_workload("pk_f32", n_seq=4, seq_len=[100, 45, 300, 77], T=522, H=4, d=64, B=16, m=4, k=32,
+                           q_dtype="f32", k_dtype="f32", mode="varlen", seed=132)
+    _run(W.pack(base))
+    base = W.make_workload("pk_long", n_seq=2, seq_len=[1001, 19003], T=20004, H=64, d=128, B=128, m=8, k=512,
+                           q_dtype="bf16", k_dtype="bf16", mode="varlen", seed=133)
+    wl = W.pack(base)
+    qs = sample_queries(wl, 24)
+    _run(wl, queries=qs, flat_queries=qs[::3])
+
+
 def test_fp32_generic_shapes():
     wl = W.make_workload("f32_odd", seq_len=777, T=777, H=3, d=20, B=16, m=5, k=50, q_dtype="f32", k_dtype="f32",
                          seed=106)
@@ -213,7 +239,7 @@ def test_block_sparse_tokens_and_iou_diagnostic():
 
 
 def test_bad_device_side_metadata_stays_in_bounds():
-    # seq_len, q_pos and block_idx live on the device and cannot be validated by the host: the
+    # seq_len, q_pos, q_lo and block_idx live on the device and cannot be validated by the host: the
     # kernels clamp them.  Whatever they hold, every call must finish and every index it writes
     # must be -1 or a position inside the padded key array.
     from paper_2603_28458_amd import hisa
@@ -250,6 +276,14 @@ def test_bad_device_side_metadata_stays_in_bounds():
     pos[1::3] = 10 ** 9
     Q2 = hisa.Queries(Q.q, Q.w, Q.dtype, q_pos=pos)
     run_all(Q2, K)
+    # 2b. first visible positions below zero, past the query, and far beyond the sequence
+    lo = torch.arange(600, dtype=torch.int32, device=dev) + 1000
+    lo[::4] = -50
+    lo[1::4] = 10 ** 9
+    lo[2::4] += 500                      # past the query's own position: it sees nothing
+    pos_ok = torch.arange(600, dtype=torch.int32, device=dev) + 1400
+    run_all(hisa.Queries(Q.q, Q.w, Q.dtype, q_pos=pos_ok, q_lo=lo), K)
+    run_all(hisa.Queries(Q.q, Q.w, Q.dtype, q_pos=pos, q_lo=lo), K)
     # 3. block ids that are negative, far too large, or repeated
     g = torch.Generator(device="cpu").manual_seed(3)
     bad = torch.randint(-100, 10 ** 6, (600, wl.m), generator=g, dtype=torch.int64).to(torch.int32)
