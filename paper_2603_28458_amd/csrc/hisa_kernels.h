@@ -514,8 +514,16 @@ __global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
   float* out = a.out + (long)blockIdx.y * a.ld;
   const int n_blocks = (int)(a.rows_per_seq / a.B);
 
-  QFrag<HG> f;
-  load_qfrag<HG>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H);
+  // the four waves share one query: its fragment is loaded (fp8 keys: converted) once, through
+  // the LDS of the tile rings, which are not in use yet
+  static_assert(sizeof(ring) >= 32 * HG * 260, "the shared query fragment is staged in the rings");
+  typename Operands<HG, KDT>::Frag fo;
+  if constexpr (KDT == DT_FP8) {
+    split_query_shared<HG, 4>((const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H, ring, wave, fo);
+  } else {
+    load_qfrag_shared<HG, 4>(fo, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H,
+                             (long)a.H * kD * 2, lds_address(ring), wave);
+  }
 
   // this wave's tiles: v = v0 + wave + 4 i; lane i looks its tile up; tiles without a visible key
   // are filled with -inf here (gather mode) and left out of the pipeline
@@ -551,9 +559,6 @@ __global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
     rows.lo = __shfl(my_row, src);
     outs.lo = __shfl(my_out, src);
   }
-  qfrag_ready<HG>(f);
-  typename Operands<HG, KDT>::Frag fo;
-  Operands<HG, KDT>::make(f, fo);
   __amdgpu_buffer_rsrc_t krsrc, srsrc;
   key_buffers<KDT>(a, seq, krsrc, srsrc);
   const uint32_t ring_addr = lds_address(ring) + wave * NB * TileGeom<KDT>::kBufBytes;
