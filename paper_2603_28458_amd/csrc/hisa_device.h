@@ -1,11 +1,16 @@
 // Device-side building blocks of the HISA indexer kernels (gfx950 / CDNA4, wave64).
 //
+//  * wave_all / wave_scan_add: wave-wide reductions and prefix sums on DPP and lane swaps.
 //  * QFrag / mfma_tile / tile_epilogue: the query-heads x key-tile contraction of Eq. 1 / Eq. 5 of
 //    the paper on the 32x32x16 bf16 MFMA, with the ReLU, gate and head-sum epilogue in registers.
-//  * tile staging: a 32-key x 128-dim key tile in LDS as 512 16-byte chunks, XOR-swizzled so that
-//    both the lane-contiguous global->LDS transfer and the MFMA-layout load are bank-conflict free.
-//  * select_topk: exact per-row top-k (Eqs. 2, 6, 9) by MSB-first radix select on order-preserving
-//    keys held in registers, ties to the lower index, output in ascending index order.
+//  * QFrag8 / split_qfrag / split_query_shared: the same contraction for fp8 keys on the fp8 MFMA
+//    (32x32x64, e4m3 x e4m3) against the bf16 query written as the sum of two e4m3 numbers.
+//  * tile staging: a 32-key x 128-dim key tile in LDS as 16-byte chunks, XOR-swizzled so that
+//    both the lane-contiguous global->LDS transfer and the MFMA-layout load are bank-conflict free;
+//    load_qfrag_shared stages the query fragment the same way, once per workgroup.
+//  * select_topk: exact per-row top-k (Eqs. 2, 6, 9) on order-preserving keys held in registers:
+//    the threshold is bracketed by key ranges cut into 256 bins; ties go to the lower index,
+//    output in ascending index order.
 //  * score_slot: the swizzled LDS position of a candidate's score, conflict-free both for the
 //    scoring waves (32 consecutive candidates) and for the selecting threads (E consecutive each).
 #pragma once
