@@ -622,6 +622,15 @@ __device__ __forceinline__ uint32_t ordered_key(float s) {
   return k ? k : 1u;
 }
 
+// The same order-preserving map without the special cases, for score arrays whose writer
+// guarantees that -0 does not occur and marks "not a candidate" with the all-ones bit pattern
+// (which this map sends to 0): three instructions instead of seven.
+constexpr uint32_t kNoCandidateBits = 0xffffffffu;
+__device__ __forceinline__ uint32_t ordered_key_plain(uint32_t bits) {
+  const uint32_t mask = (uint32_t)((int32_t)bits >> 31) | 0x80000000u;
+  return bits ^ mask;
+}
+
 __device__ __forceinline__ float key_to_score(uint32_t k) {
   const uint32_t b = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
   return __uint_as_float(b);
@@ -706,7 +715,9 @@ __device__ __forceinline__ void find_digit(const uint32_t* hist, uint32_t* bcast
 // Every thread of the workgroup must call it (it contains workgroup barriers).
 // SAFE: load4(q) may be called for any q < THREADS * E / 4 (it returns anything beyond n); the
 // loads of a thread are then issued back to back instead of one per guarded branch.
-template <int THREADS, int E, bool SAFE = false, class Load4, class Load1, class Emit>
+// FORCED: keys equal to 0xffffffff may occur (callers that force rows to the top); without it the
+// per-element bookkeeping for them is left out.
+template <int THREADS, int E, bool SAFE = false, bool FORCED = true, class Load4, class Load1, class Emit>
 __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, int k, Load4 load4,
                                            Load1 load1, Emit emit) {
   static_assert(E % 4 == 0, "elements per thread come in groups of four");
@@ -731,29 +742,35 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
       if (i0 + 4 * g < n) q4s[g] = load4((i0 >> 2) + g);
     }
   }
+  const bool whole = i0 + E <= n;   // every element of this thread lies inside the row (all but one thread)
 #pragma unroll
   for (int g = 0; g < E / 4; ++g) {
     const uint4 q4 = q4s[g];
     const uint32_t kk[4] = {q4.x, q4.y, q4.z, q4.w};
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
-      const uint32_t kj = (i0 + 4 * g + x < n) ? kk[x] : 0u;
+      const uint32_t kj = (whole || i0 + 4 * g + x < n) ? kk[x] : 0u;
       key[4 * g + x] = kj;
       cnt += kj != 0u;
-      n_top += kj == TOP;
-      // minimum / maximum over the keys in 1 .. TOP-1: 0 - 1 wraps to TOP and TOP - 1 stays large,
-      // so both ends of the key space drop out of the minimum; TOP + 1 wraps to 0 for the maximum
-      const uint32_t for_min = kj - 1u, for_max = kj + 1u;
+      // minimum over the keys in 1 .. TOP-1: 0 - 1 wraps to TOP and TOP - 1 stays large, so both
+      // ends of the key space drop out of the minimum
+      const uint32_t for_min = kj - 1u;
       t_min = for_min < t_min ? for_min : t_min;
-      t_max = for_max > t_max ? for_max : t_max;
+      if (FORCED) {
+        n_top += kj == TOP;
+        const uint32_t for_max = kj + 1u;   // TOP + 1 wraps to 0 and drops out of the maximum
+        t_max = for_max > t_max ? for_max : t_max;
+      } else {
+        t_max = kj > t_max ? kj : t_max;
+      }
     }
   }
   // t_min = (smallest key in 1..TOP-1) - 1, or >= TOP - 1 if there is none; t_max = (largest such key) + 1, or 0/1
   uint32_t lo_est = t_min >= TOP - 1u ? 0u : t_min + 1u;   // this thread's minimum, 0 if it has none
   uint32_t k_min = t_min >= TOP - 1u ? TOP : t_min + 1u;
-  uint32_t k_max = t_max <= 1u ? 0u : t_max - 1u;
+  uint32_t k_max = FORCED ? (t_max <= 1u ? 0u : t_max - 1u) : t_max;
   cnt = wave_sum(cnt);
-  n_top = wave_sum(n_top);
+  if (FORCED) n_top = wave_sum(n_top);
   lo_est = wave_max(lo_est);
   k_min = wave_min(k_min);
   k_max = wave_max(k_max);
@@ -823,14 +840,14 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
         continue;
       }
       const uint32_t bin_lo = lo + (D << s);
-      if (s == 0) {          // bins are single keys
-        tau = bin_lo;
-        r = krem;
-        break;
-      }
       if (krem == n_c) {     // the whole bin is selected
         tau = bin_lo - 1u;
         r = 0u;
+        break;
+      }
+      if (s == 0) {          // bins are single keys: krem of the n_c copies of this key are selected
+        tau = bin_lo;
+        r = krem;
         break;
       }
       const uint32_t span = (1u << s) - 1u;
@@ -848,11 +865,34 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
 
   // Positions in index order: thread t's elements precede thread t+1's, so an exclusive scan of
   // the per-thread counts (selected-for-sure, equal-to-threshold) gives every thread its base.
+  if (r == 0u) {
+    // no key equal to the threshold is taken (the usual end of the search: a bin taken whole, or
+    // everything selected): one count and one scan
+    uint32_t g_cnt = 0;
+#pragma unroll
+    for (int j = 0; j < E; ++j) g_cnt += key[j] > tau;
+    const uint32_t g_inc = wave_scan_add(g_cnt);
+    __syncthreads();   // sm.red is free again
+    if (lane == 63) sm.red[wave] = g_inc;
+    __syncthreads();
+    uint32_t g_run = g_inc - g_cnt;
+#pragma unroll
+    for (int v = 0; v < NW; ++v)
+      if (v < wave) g_run += sm.red[v];
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      if (key[j] > tau) {
+        emit((int)g_run, i0 + j, key[j]);
+        ++g_run;
+      }
+    }
+    return n_valid < k ? n_valid : k;
+  }
   uint32_t g_cnt = 0, e_cnt = 0;
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     g_cnt += key[j] > tau;
-    e_cnt += (tau != 0u && key[j] == tau);
+    e_cnt += key[j] == tau;   // (r > 0 implies tau != 0)
   }
   const uint32_t g_inc = wave_scan_add(g_cnt), e_inc = wave_scan_add(e_cnt);
   __syncthreads();   // sm.red is free again
@@ -872,7 +912,7 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     const bool gt = key[j] > tau;
-    const bool eq = tau != 0u && key[j] == tau;
+    const bool eq = key[j] == tau;
     if (gt || (eq && e_run < r)) emit((int)(g_run + (e_run < r ? e_run : r)), i0 + j, key[j]);
     g_run += gt;
     e_run += eq;

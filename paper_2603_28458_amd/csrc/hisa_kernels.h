@@ -839,7 +839,7 @@ __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
     oi[p] = id;
     if (os) os[p] = key_to_score(key);
   };
-  const int n_out = select_topk<THREADS, E, true>(sm, n, a.k, load4, load1, emit);
+  const int n_out = select_topk<THREADS, E, true, MAP == MAP_BLOCKS>(sm, n, a.k, load4, load1, emit);
   for (int p = n_out + threadIdx.x; p < a.k; p += THREADS) {
     oi[p] = -1;
     if (os) os[p] = neg_inf();
@@ -1336,7 +1336,9 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
   auto finish = [&](int j, float s) {
     const int r = rows.at(j);
     const int row = (r < 0 ? 0 : r) + (lane & 31);
-    if (row >= (r < 0 ? 0 : n_vis) || row < lo) s = neg_inf();
+    // a masked slot holds the all-ones pattern (ordered_key_plain sends it to "not a candidate");
+    // a finished score is a sum that starts from +0, so it is never -0
+    if (row >= (r < 0 ? 0 : n_vis) || row < lo) s = __uint_as_float(kNoCandidateBits);
     if (lane < 32) sc[score_slot((wave + NW * j) * 32 + lane)] = s;
   };
   const uint32_t ring_addr = lds_address(smem) + wave * NB * kTileBytes;
@@ -1347,10 +1349,11 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
   int32_t* oi = topk_idx + (long)t * k;
   float* os = topk_scores ? topk_scores + (long)t * k : nullptr;
   auto load4 = [&](int q) -> uint4 {
-    const float4 v = *reinterpret_cast<const float4*>(sc + score_slot(4 * q));
-    return make_uint4(ordered_key(v.x), ordered_key(v.y), ordered_key(v.z), ordered_key(v.w));
+    const uint4 v = *reinterpret_cast<const uint4*>(sc + score_slot(4 * q));
+    return make_uint4(ordered_key_plain(v.x), ordered_key_plain(v.y), ordered_key_plain(v.z),
+                      ordered_key_plain(v.w));
   };
-  auto load1 = [&](int i) -> uint32_t { return ordered_key(sc[score_slot(i)]); };
+  auto load1 = [&](int i) -> uint32_t { return ordered_key_plain(__float_as_uint(sc[score_slot(i)])); };
   // A thread's E consecutive candidates lie in one kept block when E divides B: its token base is
   // then fetched once, not per emitted candidate.
   const bool one_slot = a.B % E == 0;
@@ -1373,7 +1376,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
     stage[p] = tok;
     if (os) os[p] = key_to_score(key);
   };
-  const int n_out = select_topk<NT, E>(sm, n_cand_slots, k, load4, load1, emit);
+  const int n_out = select_topk<NT, E, false, false>(sm, n_cand_slots, k, load4, load1, emit);
   for (int p = n_out + threadIdx.x; p < k; p += NT) {
     stage[p] = -1;
     if (os) os[p] = neg_inf();
