@@ -689,12 +689,6 @@ __device__ __forceinline__ void find_bin(const uint32_t* hist, uint32_t* bcast, 
   }
 }
 
-// The digit variant used by the streaming select (bins = one radix digit).
-__device__ __forceinline__ void find_digit(const uint32_t* hist, uint32_t* bcast, uint32_t krem,
-                                           int lane) {
-  find_bin(hist, bcast, krem, lane);
-}
-
 // Exact top-k of one row by one workgroup of THREADS threads, n <= THREADS * E elements.
 //   load4(q) -> keys of elements 4q .. 4q+3 (0: not a candidate); load1(i) -> key of element i.
 //   Thread t holds the E consecutive elements t*E .. t*E+E-1 in registers.

@@ -765,7 +765,7 @@ struct SelectArgs {
 template <int THREADS, int E, int MAP>
 __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
   __shared__ SelectSmem<THREADS, E> sm;
-  // Rows of up to 8192 entries are also kept in LDS as keys: the later radix passes re-read single
+  // Rows of up to 8192 entries are also kept in LDS as keys: the later threshold passes re-read single
   // entries, and from global memory every such round costs a full memory latency (it is what a
   // decode step, with one workgroup per query, mostly waited for).
   constexpr bool kStaged = THREADS * E * 4 <= 32768;
@@ -1138,7 +1138,7 @@ __global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(Sel
   const int nc_all = (int)(base_c < (uint32_t)CAP ? base_c : (uint32_t)CAP);
   if (!equal_mode && r > 0u && nc_all <= THREADS) {
     // the usual case, a short list: one candidate per thread, ranked by counting the candidates
-    // that beat it (larger key, or equal key earlier in the list); no radix passes
+    // that beat it (larger key, or equal key earlier in the list); no further passes
     uint32_t* flag = reinterpret_cast<uint32_t*>(&sm);   // [THREADS] selected flags
     const uint32_t mykey = tid < nc_all ? cand_key[tid] : 0u;
     uint32_t rank = 0;
