@@ -572,17 +572,22 @@ __global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
 }
 
 // Eq. 1 / Eq. 5 on MFMA for a causal prefill of ONE sequence with consecutive positions: one
-// workgroup of 8 waves = 8 consecutive queries; 64-key tiles (two 32-key sub-tiles) are DMA'd once
-// into LDS (double buffered, one barrier per tile) and shared by the 8 queries; each wave runs the
-// MFMAs of one sub-tile over the epilogue of the previous one (two accumulator sets).  Longest
-// prefixes launch first.  Used by the flat DSA indexer and by Stage 1.  (Measured and not kept:
-// score stores deferred by one iteration so that the wait before the barrier finds them old, and
-// on top of that three tile buffers with the LDS operand reads requested one sub-tile early: the
-// flat indexer gains 2 % and 4 %, Stage 1, whose rows are at most 8 tiles long, loses 3 %.)
+// workgroup of 8 waves = 8 consecutive queries; 128-key tiles (four 32-key sub-tiles) are DMA'd
+// once into LDS (double buffered, one barrier per tile) and shared by the 8 queries; each wave runs
+// the MFMAs of one sub-tile over the epilogue of the previous one (two accumulator sets).  Longest
+// prefixes launch first.  Used by the flat DSA indexer and by Stage 1 above 512 blocks.  (Tiles of
+// 64 keys, i.e. twice the barriers, were 2-3 % slower on the 64K flat indexer and 9 % on the 1M
+// chunk.  Measured and not kept: score stores deferred by one iteration so that the wait before
+// the barrier finds them old, and on top of that three tile buffers with the LDS operand reads
+// requested one sub-tile early: +2 % and +4 % on the flat indexer, -3 % on short Stage 1 rows.
+// With the DMA, the stores and the barrier all removed the loop itself runs at 1.34 PFLOP/s:
+// what is left is the issue-slot limit of the MFMA / epilogue mix, not memory.)
 template <int HG, int KDT>
 __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
   constexpr int BB = TileGeom<KDT>::kBufBytes;
-  __shared__ __align__(16) unsigned char tiles[2 * 2 * BB];   // [buffer][sub-tile]
+  constexpr int SUBS = 4;                       // 32-key sub-tiles per staged tile (one barrier per tile)
+  constexpr int TK = 32 * SUBS;                 // keys per tile
+  __shared__ __align__(16) unsigned char tiles[2 * SUBS * BB];   // [buffer][sub-tile]
   const int g = gridDim.x - 1 - blockIdx.x;
   const int th = threadIdx.x, lane = th & 63;
   const int wave = __builtin_amdgcn_readfirstlane(th >> 6);
@@ -595,7 +600,7 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
   const int tl_last = (g * 8 + 7) < a.t_count ? (g * 8 + 7) : a.t_count - 1;
   int seq_last;
   const int n_max = visible_rows(a, query_pos(a, a.t_begin + tl_last, seq_last));
-  const int n_iter = (n_max + 63) >> 6;
+  const int n_iter = (n_max + TK - 1) / TK;
   float* out = a.out + (long)(active ? tl : 0) * a.ld;
 
   QFrag<HG> fq;
@@ -604,38 +609,41 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
   __amdgpu_buffer_rsrc_t krsrc, srsrc;
   key_buffers<KDT>(a, 0, krsrc, srsrc);
   const uint32_t tiles_addr = lds_address(tiles);
-  // this wave's share of the cooperative DMA of a 64-key tile: sub-tile wave / 4, an eighth of it
-  const int sub_w = wave >> 2, part_w = wave & 3;
-  int voff[2] = {0, 0};
+  // this wave's share of the cooperative DMA of a tile: sub-tile wave / 2, rows 16 * (wave % 2) .. +15 of it
+  const int sub_w = wave >> 1, part_w = wave & 1;
+  int voff[4] = {0, 0, 0, 0};
   if (KDT == DT_BF16) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int r = part_w * 8 + i * 4 + (lane >> 4), c = lane & 15;
+    for (int i = 0; i < 4; ++i) {               // four transfers of four rows
+      const int r = part_w * 16 + i * 4 + (lane >> 4), c = lane & 15;
       voff[i] = (lane >> 4) * 256 + ((c ^ (r & 15)) << 4);
     }
   } else {
-    // transfer part_w of the sub-tile: rows 8*part_w + lane/8, swizzled by (row / 2) % 8
-    voff[0] = (lane >> 3) * 128 + (((lane & 7) ^ ((part_w * 4 + (lane >> 4)) & 7)) << 4);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)                 // two transfers of eight rows, swizzled by (row / 2) % 8
+      voff[i] = (lane >> 3) * 128 + (((lane & 7) ^ (((part_w * 2 + i) * 4 + (lane >> 4)) & 7)) << 4);
   }
   auto dma_tile = [&](int it, int buf) {
-    const uint32_t dst = tiles_addr + (buf * 2 + sub_w) * BB;
-    const int row0 = it * 64 + sub_w * 32 + part_w * 8;
+    const uint32_t dst = tiles_addr + (buf * SUBS + sub_w) * BB;
+    const int row0 = it * TK + sub_w * 32 + part_w * 16;
     if constexpr (KDT == DT_BF16) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, (lds_void*)(uintptr_t)(dst + (part_w * 128 + i * 64) * 16),
+      for (int i = 0; i < 4; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, (lds_void*)(uintptr_t)(dst + (part_w * 256 + i * 64) * 16),
                                                  16, voff[i], (row0 + i * 4) * 256, 0, 0);
     } else {
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, (lds_void*)(uintptr_t)(dst + part_w * 1024), 16, voff[0],
-                                               row0 * 128, 0, 0);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(krsrc, (lds_void*)(uintptr_t)(dst + (part_w * 2 + i) * 1024), 16,
+                                                 voff[i], (row0 + i * 8) * 128, 0, 0);
       if (part_w == 0)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(srsrc, (lds_void*)(uintptr_t)(dst + 4096), 4, lane * 4,
-                                                 (it * 64 + sub_w * 32) * 4, 0, 0);
+                                                 (it * TK + sub_w * 32) * 4, 0, 0);
     }
   };
   using Tile = typename Operands<HG, KDT>::Tile;
   auto read_sub = [&](int buf, int sub, float& scale) -> Tile {
-    const uint32_t addr = tiles_addr + (buf * 2 + sub) * BB;
+    const uint32_t addr = tiles_addr + (buf * SUBS + sub) * BB;
     if constexpr (KDT == DT_BF16) {
       scale = 1.f;
       return lds_read_tile_raw(addr);
@@ -661,20 +669,23 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
   for (int it = 0; it < n_iter; ++it) {
     const int buf = it & 1;
     if (it + 1 < n_iter) dma_tile(it + 1, buf ^ 1);
-    {
-      const Tile kv = read_sub(buf, 0, sc_b);
-      acc_b = mfma_tile(f, kv);                                        // sub-tile 2it
-      if (it > 0) finish(2 * it - 1, tile_epilogue<HG>(f, acc_a) * sc_a);  // previous tile's second half
-    }
-    {
-      const Tile kv = read_sub(buf, 1, sc_a);
-      acc_a = mfma_tile(f, kv);                                        // sub-tile 2it+1
-      finish(2 * it, tile_epilogue<HG>(f, acc_b) * sc_b);
+#pragma unroll
+    for (int h = 0; h < SUBS / 2; ++h) {
+      {
+        const Tile kv = read_sub(buf, 2 * h, sc_b);
+        acc_b = mfma_tile(f, kv);                                                  // sub-tile SUBS*it + 2h
+        if (it > 0 || h > 0) finish(SUBS * it + 2 * h - 1, tile_epilogue<HG>(f, acc_a) * sc_a);   // the one before
+      }
+      {
+        const Tile kv = read_sub(buf, 2 * h + 1, sc_a);
+        acc_a = mfma_tile(f, kv);                                                  // sub-tile SUBS*it + 2h + 1
+        finish(SUBS * it + 2 * h, tile_epilogue<HG>(f, acc_b) * sc_b);
+      }
     }
     wait_vmem_le<0>();   // the next tile (and this wave's score stores) have landed
     __syncthreads();
   }
-  if (n_iter > 0) finish(2 * n_iter - 1, tile_epilogue<HG>(f, acc_a) * sc_a);
+  if (n_iter > 0) finish(SUBS * n_iter - 1, tile_epilogue<HG>(f, acc_a) * sc_a);
 }
 
 // ------------------------------------------------------------------------------------------
