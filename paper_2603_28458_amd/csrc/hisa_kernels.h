@@ -696,6 +696,9 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
 // what is left per query is its 16 KB fragment from HBM, and eight waves per CU with one such load
 // in flight each keep that stream busy while the others compute.  Workgroup g serves the 8 * NQ
 // consecutive queries from 8 * NQ * g, wave w the queries w, w + 8, ...; longest prefixes first.
+// (Measured and not kept: pulling the next query's fragment towards L2 while the current one is
+// scored, by DMA into a dummy LDS area since there are no registers for a second fragment: 10 %
+// slower, the extra transfers cost more than the shorter wait.)
 template <int HG, int NQ>
 __global__ __launch_bounds__(512) void k_score_resident(ScoreArgs a) {
   extern __shared__ __align__(16) unsigned char tiles[];   // [n_sub][8192]
