@@ -343,20 +343,38 @@ __device__ __forceinline__ void split_qfrag(const QFrag<HG>& f, QFrag8<HG>& o) {
 // bytes, lane-contiguous).  lds: 32*HG*260 bytes that nothing else touches until the function
 // returns (it ends with a second barrier).  q, w: this query's [H, d] bf16 and [H] gates.
 template <int HG, int NW>
-__device__ __forceinline__ void split_query_shared(const uint16_t* __restrict__ q, const float* __restrict__ w,
-                                                   unsigned char* lds, int wave, QFrag8<HG>& o) {
-  constexpr int H = 32 * HG;
-  constexpr int HP = H / NW;     // heads per wave
-  constexpr int LPH = 64 / HP;   // lanes per head
-  constexpr int EPL = kD / LPH;  // elements per lane
+struct SplitShare {
+  static constexpr int H = 32 * HG;
+  static constexpr int HP = H / NW;     // heads per wave
+  static constexpr int LPH = 64 / HP;   // lanes per head
+  static constexpr int EPL = kD / LPH;  // elements per lane
   static_assert(H % NW == 0 && (LPH == 4 || LPH == 8 || LPH == 16), "a head must map to 4, 8 or 16 lanes");
+  uint4 v[EPL / 8];   // this lane's share of its head, as loaded
+  float gate;
+};
+
+// First half: the loads only, so that a caller can put other memory traffic behind them.
+template <int HG, int NW>
+__device__ __forceinline__ void split_query_request(SplitShare<HG, NW>& r, const uint16_t* __restrict__ q,
+                                                    const float* __restrict__ w, int wave) {
+  using S = SplitShare<HG, NW>;
+  const int lane = lane_id();
+  const int head = wave * S::HP + lane / S::LPH, seg = lane % S::LPH;
+  const uint4* src = reinterpret_cast<const uint4*>(q + head * kD + seg * S::EPL);
+#pragma unroll
+  for (int c = 0; c < S::EPL / 8; ++c) r.v[c] = src[c];
+  r.gate = w[head];
+}
+
+template <int HG, int NW>
+__device__ __forceinline__ void split_query_complete(const SplitShare<HG, NW>& share, unsigned char* lds, int wave,
+                                                     QFrag8<HG>& o) {
+  using S = SplitShare<HG, NW>;
+  constexpr int HP = S::HP, LPH = S::LPH, EPL = S::EPL;
   const int lane = lane_id();
   const int head = wave * HP + lane / LPH, seg = lane % LPH;
-  uint4 v[EPL / 8];
-  const uint4* src = reinterpret_cast<const uint4*>(q + head * kD + seg * EPL);
-#pragma unroll
-  for (int c = 0; c < EPL / 8; ++c) v[c] = src[c];
-  const float gate = w[head];
+  const uint4* v = share.v;
+  const float gate = share.gate;
   uint32_t mag = 0;
 #pragma unroll
   for (int c = 0; c < EPL / 8; ++c) {
@@ -426,6 +444,14 @@ __device__ __forceinline__ void split_query_shared(const uint16_t* __restrict__ 
     }
   }
   __syncthreads();
+}
+
+template <int HG, int NW>
+__device__ __forceinline__ void split_query_shared(const uint16_t* __restrict__ q, const float* __restrict__ w,
+                                                   unsigned char* lds, int wave, QFrag8<HG>& o) {
+  SplitShare<HG, NW> r;
+  split_query_request<HG, NW>(r, q, w, wave);
+  split_query_complete<HG, NW>(r, lds, wave, o);
 }
 
 template <int HG>
@@ -582,9 +608,9 @@ __device__ __forceinline__ void wait_vmem_le() {
 // (row, half) at step kk is chunk 2*kk + half of its row, which is what lds_read_tile_raw returns.
 // lds: HG * 8192 bytes nothing else touches until the function returns (it ends with a barrier).
 template <int HG, int NW>
-__device__ __forceinline__ void load_qfrag_shared(QFrag<HG>& f, const uint16_t* __restrict__ q,
-                                                  const float* __restrict__ w, long q_bytes_left,
-                                                  uint32_t lds_addr, int wave) {
+__device__ __forceinline__ void qfrag_shared_request(QFrag<HG>& f, const uint16_t* __restrict__ q,
+                                                     const float* __restrict__ w, long q_bytes_left,
+                                                     uint32_t lds_addr, int wave) {
   const int lane = lane_id();
   const int half = lane >> 5;
   const __amdgpu_buffer_rsrc_t qrsrc = key_buffer(q, q_bytes_left);
@@ -599,6 +625,12 @@ __device__ __forceinline__ void load_qfrag_shared(QFrag<HG>& f, const uint16_t* 
   for (int g = 0; g < HG; ++g)
 #pragma unroll
     for (int i = 0; i < 16; ++i) f.w[g][i] = w[g * 32 + 8 * (i >> 2) + 4 * half + (i & 3)];
+}
+
+// Second half: waits for everything this wave has in flight (the request above and whatever the
+// caller issued since, e.g. its first key tile), then reads the fragment.  Ends with a barrier.
+template <int HG>
+__device__ __forceinline__ void qfrag_shared_complete(QFrag<HG>& f, uint32_t lds_addr) {
   wait_vmem_le<0>();
   __syncthreads();
 #pragma unroll
@@ -609,6 +641,14 @@ __device__ __forceinline__ void load_qfrag_shared(QFrag<HG>& f, const uint16_t* 
       f.a[g][kk] = as_bf16x8(make_uint4(t[4 * kk + 0], t[4 * kk + 1], t[4 * kk + 2], t[4 * kk + 3]));
   }
   __syncthreads();
+}
+
+template <int HG, int NW>
+__device__ __forceinline__ void load_qfrag_shared(QFrag<HG>& f, const uint16_t* __restrict__ q,
+                                                  const float* __restrict__ w, long q_bytes_left,
+                                                  uint32_t lds_addr, int wave) {
+  qfrag_shared_request<HG, NW>(f, q, w, q_bytes_left, lds_addr, wave);
+  qfrag_shared_complete<HG>(f, lds_addr);
 }
 
 

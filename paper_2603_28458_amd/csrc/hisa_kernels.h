@@ -403,11 +403,23 @@ struct Operands<HG, DT_FP8> {
   static __device__ __forceinline__ void make(const QFrag<HG>& f, Frag& o) { split_qfrag<HG>(f, o); }
 };
 
+// One key tile (32 rows from `row`) global -> LDS at lds_addr, in the staged layout of its key type.
+template <int KDT>
+__device__ __forceinline__ void tile_dma(__amdgpu_buffer_rsrc_t krsrc, __amdgpu_buffer_rsrc_t srsrc,
+                                         uint32_t lds_addr, int row) {
+  if constexpr (KDT == DT_BF16)
+    tile_dma_bf16(krsrc, lds_addr, row * (kD * 2), tile_lane_offsets_bf16());
+  else
+    tile_dma_fp8(krsrc, srsrc, lds_addr, row);
+}
+
+// primed: the caller has already issued the DMA of tile 0 into ring slot 0 (tile_dma above), to
+// overlap it with other loads of its own.
 template <int HG, int KDT, int NB, class RowAt, class Finish>
 __device__ __forceinline__ void wave_pipeline(const typename Operands<HG, KDT>::Frag& f,
                                               __amdgpu_buffer_rsrc_t krsrc,
                                               __amdgpu_buffer_rsrc_t srsrc, uint32_t ring_addr, int nj,
-                                              RowAt row_at, Finish finish) {
+                                              RowAt row_at, Finish finish, bool primed = false) {
   static_assert(NB >= 1 && NB <= 3, "ring of one to three tiles");
   constexpr int L = TileGeom<KDT>::kLoads;
   constexpr int BB = TileGeom<KDT>::kBufBytes;
@@ -441,7 +453,7 @@ __device__ __forceinline__ void wave_pipeline(const typename Operands<HG, KDT>::
   if (nj <= 0) return;
 #pragma unroll
   for (int b = 0; b < NB; ++b)
-    if (b < nj) dma(b, b);
+    if (b < nj && !(primed && b == 0)) dma(b, b);
   int buf = 0;                       // ring slot of the tile the next step consumes
   float sc_a = 1.f, sc_b = 1.f;      // fp8: per-key scales of the tiles held in acc_a / acc_b
   // one step: tile jn -> acc_out (matrix cores) while tile jn-1 = acc_in is finished (vector ALU)
@@ -1297,10 +1309,22 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
   constexpr bool kSharedSplit = KDT == DT_FP8 && E1 == 0;
   static_assert(!kSharedSplit || kStageBytes >= (size_t)32 * HG * 260, "the shared fragment is built in the rings");
   static_assert(kStageBytes >= (size_t)HG * 8192, "the shared query fragment is staged in the rings");
+  // Without Stage 1 in this launch the fragment is staged in the score area when that is large
+  // enough (it is free until the first score lands), which leaves the rings free: each wave then
+  // issues its first key tile BEHIND the query request and waits for both at once.
+  const uint16_t* q_t = (const uint16_t*)a.q + (long)t * a.H * kD;
+  const float* w_t = a.w + (long)t * a.H;
+  const bool q_in_sc = E1 == 0 && (long)a.m * a.B * 4 >= (long)32 * HG * 260;
+  unsigned char* q_lds = q_in_sc ? reinterpret_cast<unsigned char*>(sc) : smem;
   QFrag<HG> f;
-  if constexpr (!kSharedSplit)
-    load_qfrag_shared<HG, NW>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H,
-                              (long)a.H * kD * 2, lds_address(smem), wave);
+  SplitShare<HG, NW> q_share;
+  if constexpr (kSharedSplit) {
+    split_query_request<HG, NW>(q_share, q_t, w_t, wave);
+  } else if constexpr (E1 == 0) {
+    qfrag_shared_request<HG, NW>(f, q_t, w_t, (long)a.H * kD * 2, lds_address(q_lds), wave);
+  } else {
+    load_qfrag_shared<HG, NW>(f, q_t, w_t, (long)a.H * kD * 2, lds_address(smem), wave);
+  }
 
   const int tpb = a.B >> 5;
   const int n_blocks = (int)(a.rows_per_seq / a.B);
@@ -1334,19 +1358,25 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
   LaneTable rows;
   rows.lo = row_of(wave + NW * (lane < nj ? lane : 0));
   rows.hi = (nj > 64) ? row_of(wave + NW * (lane + 64 < nj ? lane + 64 : 0)) : -1;
-  typename Operands<HG, KDT>::Frag fo;
-  if constexpr (kSharedSplit) {
-    split_query_shared<HG, NW>((const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H, smem, wave, fo);
-  } else {
-    qfrag_ready<HG>(f);
-    Operands<HG, KDT>::make(f, fo);
-  }
   __amdgpu_buffer_rsrc_t krsrc, srsrc;
   key_buffers<KDT>(a, seq, krsrc, srsrc);
   auto row_at = [&](int j) {
     const int r = rows.at(j);
     return r < 0 ? 0 : r;   // a tile without visible keys still flows through, masked below
   };
+  const uint32_t ring_addr = lds_address(smem) + wave * NB * kTileBytes;
+  const bool primed = q_in_sc && nj > 0;
+  if (primed) tile_dma<KDT>(krsrc, srsrc, ring_addr, row_at(0));
+  typename Operands<HG, KDT>::Frag fo;
+  if constexpr (kSharedSplit) {
+    split_query_complete<HG, NW>(q_share, q_lds, wave, fo);
+  } else if constexpr (E1 == 0) {
+    qfrag_shared_complete<HG>(f, lds_address(q_lds));
+    Operands<HG, KDT>::make(f, fo);
+  } else {
+    qfrag_ready<HG>(f);
+    Operands<HG, KDT>::make(f, fo);
+  }
   auto finish = [&](int j, float s) {
     const int r = rows.at(j);
     const int row = (r < 0 ? 0 : r) + (lane & 31);
@@ -1355,8 +1385,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
     if (row >= (r < 0 ? 0 : n_vis) || row < lo) s = __uint_as_float(kNoCandidateBits);
     if (lane < 32) sc[score_slot((wave + NW * j) * 32 + lane)] = s;
   };
-  const uint32_t ring_addr = lds_address(smem) + wave * NB * kTileBytes;
-  wave_pipeline<HG, KDT, NB>(fo, krsrc, srsrc, ring_addr, nj, row_at, finish);
+  wave_pipeline<HG, KDT, NB>(fo, krsrc, srsrc, ring_addr, nj, row_at, finish, primed);
   __syncthreads();   // scores complete, rings dead: the select scratch may overwrite them
   const int n_cand_slots = n_active * 32;   // score slots actually written
 
