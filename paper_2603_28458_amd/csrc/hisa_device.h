@@ -620,7 +620,7 @@ __device__ __forceinline__ void qfrag_shared_request(QFrag<HG>& f, const uint16_
   for (int i = 0; i < 8 * HG; ++i)
     if (i % NW == wave)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(qrsrc, (lds_void*)(uintptr_t)(lds_addr + i * 1024), 16,
-                                               (int)lane_offs[i & 7], (i >> 3) * 8192, 0, 0);
+                                               (int)lane_offs[i & 7], (i >> 3) * 8192, 0, 2);   // aux 2 = non-temporal: a query is read once
 #pragma unroll
   for (int g = 0; g < HG; ++g)
 #pragma unroll

@@ -1426,9 +1426,12 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
   }
   __syncthreads();
   if ((k & 3) == 0 && (reinterpret_cast<uintptr_t>(oi) & 15) == 0) {
-    const int4* src = reinterpret_cast<const int4*>(stage);
-    int4* dst = reinterpret_cast<int4*>(oi);
-    for (int p = threadIdx.x; p < (k >> 2); p += NT) dst[p] = src[p];
+    // whole 16-byte rows, marked non-temporal: the indices are not read again by this kernel and
+    // should not push key tiles out of the L2
+    typedef int i32x4n __attribute__((ext_vector_type(4)));
+    const i32x4n* srcv = reinterpret_cast<const i32x4n*>(stage);
+    i32x4n* dstv = reinterpret_cast<i32x4n*>(oi);
+    for (int p = threadIdx.x; p < (k >> 2); p += NT) __builtin_nontemporal_store(srcv[p], dstv + p);
   } else {
     for (int p = threadIdx.x; p < k; p += NT) oi[p] = stage[p];
   }
