@@ -555,7 +555,6 @@ __global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
   // compact the valid tiles to the low lanes (order does not matter)
   const uint64_t okmask = __ballot(my_row >= 0);
   const int nj = __popcll(okmask);
-  const int dst = (int)lanes_below(okmask);
   LaneTable rows{-1, -1}, outs{0, 0};
   {
     // lane j fetches the j-th valid entry: the source lane is the j-th set bit of okmask
@@ -567,7 +566,6 @@ __global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
       mrem &= mrem - 1;
       if (lane == q) src = bit;
     }
-    (void)dst;
     rows.lo = __shfl(my_row, src);
     outs.lo = __shfl(my_out, src);
   }
