@@ -283,6 +283,14 @@ def main():
                 "traffic": None}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["ms_per_launch"] = ms_s2
+    kbytes = {"bf16": 2, "fp8_e4m3": 1, "f32": 4}[wl.k_dtype] * wl.d + (4 if wl.k_dtype == "fp8_e4m3" else 0)
+    qbytes = wl.H * wl.d * (2 if wl.q_dtype == "bf16" else 4) + wl.H * 4
+    # key tiles that reach the compute units (from L2 / Infinity Cache / HBM) for the pairs scored
+    roof["tile_delivery_GBs"] = p2 * kbytes / (ms_s2 * 1e-3) / 1e9
+    # bytes the step has to move through HBM at least: keys (those of kept blocks, at most all) and pooled keys once, the queries once
+    # per stage, the block ids written and read, the top-k indices written
+    hbm_bytes = (min(int(wl.seq_len.sum()), p2) * kbytes + int(wl.seq_len.sum()) // wl.B * wl.d * 2
+                 + 2 * T * qbytes + 2 * T * wl.m * 4 + T * wl.k * 4)
     roof["traffic"] = measured_traffic(a.workload)
     # what this chip delivers to a kernel that does nothing else: a 1 GiB streaming copy and a loop
     # of MFMAs only (the library's probe kernels), for the fraction of the ATTAINABLE peak
@@ -317,6 +325,8 @@ def main():
                         "hisa_tflop": (p1 + p2) * flop_pair / 1e12, "flat_tflop": pf * flop_pair / 1e12},
         "roofline": roof,
         "attainable": attainable,
+        "hbm_step": {"algorithmic_bytes": hbm_bytes, "GBs": hbm_bytes / (ms_step * 1e-3) / 1e9,
+                     "frac_of_peak": hbm_bytes / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS},
     }
 
     if not a.no_flat:
