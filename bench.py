@@ -176,6 +176,44 @@ def sweep(a, torch, hisa, W):
         torch.cuda.empty_cache()
 
 
+def variant_line(name, steps, warmup, flat_steps, torch, hisa, W):
+    """The same step on another variant of the headline configuration (BASELINE's 64K prefill has
+    two: bf16 keys, and fp8 e4m3 keys with per-token scales), timed the same way, in short form."""
+    wl = W.config(name)
+    Q, K = hisa.to_device(wl)
+    pd = hisa.DTYPE_CODE[wl.pooled_dtype]
+    T, dev = wl.T, Q.q.device
+    pooled = torch.zeros((wl.n_seq, wl.s_max // wl.B, wl.d), dtype=torch.bfloat16, device=dev)
+    block_idx = torch.empty((T, wl.m), dtype=torch.int32, device=dev)
+    topk_idx = torch.empty((T, wl.k), dtype=torch.int32, device=dev)
+    ws1 = torch.empty(max(1, hisa.hisa_workspace_bytes(hisa.OP_BLOCK_SCORE_TOPK, Q, K, wl.B, wl.m, wl.k)),
+                      dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(max(1, hisa.hisa_workspace_bytes(hisa.OP_TOKEN_REFINE_TOPK, Q, K, wl.B, wl.m, wl.k)),
+                      dtype=torch.uint8, device=dev)
+    ws_f = torch.empty(hisa.hisa_workspace_bytes(hisa.OP_FLAT_TOPK, Q, K, 1, 0, wl.k), dtype=torch.uint8, device=dev)
+
+    def stage2():
+        hisa.hisa_token_refine_topk(Q, K, wl.B, wl.m, block_idx, wl.k, topk_idx=topk_idx, ws=ws2)
+
+    def step():
+        hisa.hisa_pool_blocks(K, wl.B, pooled=pooled, pooled_dtype=pd)
+        hisa.hisa_block_score_topk(Q, K, pooled, pd, wl.B, wl.m, block_idx=block_idx, ws=ws1)
+        stage2()
+
+    ms_step, _ = time_region(step, steps, warmup)
+    ms_s2, _ = time_region(stage2, steps, 1)
+    ms_flat, _ = time_region(lambda: hisa.dsa_flat_indexer_topk(Q, K, wl.k, topk_idx=topk_idx, ws=ws_f), flat_steps, 1)
+    _, p2, _ = algorithmic_pairs(wl)
+    fp8 = wl.k_dtype == "fp8_e4m3"
+    peak = PEAK_FP8_TFLOPS if fp8 else PEAK_BF16_TFLOPS
+    achieved = p2 * 2.0 * wl.H * wl.d / (ms_s2 * 1e-3) / 1e12
+    return {"workload": name, "dtype": "fp8" if fp8 else "bf16", "value": T / (ms_step * 1e-3), "unit": "queries/s",
+            "ms_per_step": ms_step, "stage2_ms": ms_s2,
+            "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                         "frac": achieved / peak, "traffic": measured_traffic(name)},
+            "flat_ms": ms_flat, "speedup_vs_flat": ms_flat / ms_step}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -349,6 +387,10 @@ def main():
             out["needles"] = needle_recall(wl, block_idx, topk_idx, flat_idx)
         del ws_f
 
+    if a.workload == "prefill64k_bf16" and not a.no_flat:
+        del Q, K, pooled, block_idx, topk_idx, ws1, ws2
+        torch.cuda.empty_cache()
+        out["fp8_keys_variant"] = variant_line("prefill64k_fp8", a.steps, a.warmup, a.flat_steps, torch, hisa, W)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out), flush=True)
