@@ -4,6 +4,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "hisa_kernels.h"
 
 using namespace hisa;
@@ -15,6 +17,26 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? HISA_OK : HISA_ERR_LAUNCH; }
 
 constexpr int kMaxK = 8192, kMaxM = 1024, kMaxCand = 65536;
+constexpr int kMaxT = 1 << 22;        // queries per call
+constexpr int kMaxSeq = 65535;        // sequences per key array (the y extent of the pooling grids)
+constexpr long kMaxGrid = 1L << 30;   // workgroups per launch (the x extent of a grid stops at 2^31 - 1)
+constexpr int kMaxDevices = 64;
+
+// A kernel that asks for more than 64 KB of dynamic LDS needs its limit raised first.  Done once
+// per kernel instance and device (again only if a later call needs more than any earlier one), not
+// on every call.
+template <auto Kern>
+int raise_lds_limit(size_t bytes) {
+  static std::atomic<int> granted[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HISA_ERR_LAUNCH;
+  if ((int)bytes <= granted[dev].load(std::memory_order_acquire)) return HISA_OK;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(Kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          (int)bytes) != hipSuccess)
+    return HISA_ERR_LAUNCH;
+  granted[dev].store((int)bytes, std::memory_order_release);
+  return HISA_OK;
+}
 
 // Flat top-k over rows longer than one select pass holds: the k best of every 65536-entry
 // segment, then the k best of those.  (16384-entry segments were measured slower: 53.5 ms against
@@ -39,14 +61,14 @@ int pick_path(int q_dtype, int k_dtype, int H, int d, int* status) {
 
 int check_queries(const hisa_queries* q) {
   if (!q || !q->q || !q->w) return HISA_ERR_NULL;
-  if (q->T < 1 || q->H < 1) return HISA_ERR_SHAPE;
+  if (q->T < 1 || q->T > kMaxT || q->H < 1) return HISA_ERR_SHAPE;
   if (!aligned16(q->q)) return HISA_ERR_ALIGN;
   return HISA_OK;
 }
 
 int check_keys(const hisa_keys* k, bool need_data) {
   if (!k || !k->seq_len) return HISA_ERR_NULL;
-  if (k->n_seq < 1 || k->s_max < 1 || k->d < 1) return HISA_ERR_SHAPE;
+  if (k->n_seq < 1 || k->n_seq > kMaxSeq || k->s_max < 1 || k->d < 1) return HISA_ERR_SHAPE;
   if (k->k_dtype < HISA_F32 || k->k_dtype > HISA_FP8_E4M3) return HISA_ERR_DTYPE;
   // one sequence's key array is addressed with 32-bit byte offsets (buffer descriptors)
   const long elem = k->k_dtype == HISA_F32 ? 4 : (k->k_dtype == HISA_BF16 ? 2 : 1);
@@ -79,14 +101,15 @@ ScoreArgs base_args(const hisa_queries* q, const hisa_keys* k) {
   a.m = 0;
   a.B = 1;
   a.tiles_per_wave = 1;
+  a.groups = 1;
   return a;
 }
 
 // ---- scoring launches -------------------------------------------------------------------
 template <int KDT>
-void launch_ranges_mfma(const ScoreArgs& a, int n_tiles_max, hipStream_t st) {
-  const int groups = (n_tiles_max + 4 * a.tiles_per_wave - 1) / (4 * a.tiles_per_wave);
-  dim3 grid(groups, a.t_count);
+void launch_ranges_mfma(ScoreArgs a, int n_tiles_max, hipStream_t st) {
+  a.groups = (n_tiles_max + 4 * a.tiles_per_wave - 1) / (4 * a.tiles_per_wave);
+  dim3 grid((unsigned)((long)a.groups * a.t_count));
   if (a.H == 64)
     hipLaunchKernelGGL((k_score_ranges<2, KDT>), grid, dim3(256), 0, st, a);
   else
@@ -108,7 +131,8 @@ void launch_score(int path, int key_dt, ScoreArgs a, long n_rows_max, bool conse
                   hipStream_t st) {
   if (path == PATH_F32) {
     const int per_wg = 1024;
-    dim3 grid((unsigned)((n_rows_max + per_wg - 1) / per_wg), a.t_count);
+    a.groups = (int)((n_rows_max + per_wg - 1) / per_wg);
+    dim3 grid((unsigned)((long)a.groups * a.t_count));
     const size_t sh = ((size_t)a.H * a.d + a.H) * sizeof(float);
     hipLaunchKernelGGL(k_score_ranges_f32, grid, dim3(256), sh, st, a, per_wg);
     return;
@@ -119,13 +143,14 @@ void launch_score(int path, int key_dt, ScoreArgs a, long n_rows_max, bool conse
     constexpr int NQ = 8;
     const size_t sh = (size_t)((a.rows_per_seq + 31) / 32) * 8192;
     dim3 grid((a.t_count + 8 * NQ - 1) / (8 * NQ));
-    auto launch = [&](auto kern) {
-      // a refusal here makes the launch below fail, which the entry point reports (launch_status)
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh);
-      hipLaunchKernelGGL(kern, grid, dim3(512), sh, st, a);
-    };
-    if (a.H == 64) launch(k_score_resident<2, NQ>);
-    else launch(k_score_resident<1, NQ>);
+    // (a refusal to raise the LDS limit makes the launch fail, which the entry point reports)
+    if (a.H == 64) {
+      (void)raise_lds_limit<k_score_resident<2, NQ>>(sh);
+      hipLaunchKernelGGL((k_score_resident<2, NQ>), grid, dim3(512), sh, st, a);
+    } else {
+      (void)raise_lds_limit<k_score_resident<1, NQ>>(sh);
+      hipLaunchKernelGGL((k_score_resident<1, NQ>), grid, dim3(512), sh, st, a);
+    }
     return;
   }
   if (!gather && consecutive && a.t_count >= 64) {
@@ -146,7 +171,7 @@ void launch_score(int path, int key_dt, ScoreArgs a, long n_rows_max, bool conse
 // ---- selection launches -----------------------------------------------------------------
 template <int MAP>
 int launch_select(const SelectArgs& a, int rows, int n_max, hipStream_t st) {
-  dim3 grid(a.n_seg, rows);
+  dim3 grid((unsigned)((long)a.n_seg * rows));
   if (n_max <= 512)
     hipLaunchKernelGGL((k_select<64, 8, MAP>), grid, dim3(64), 0, st, a);
   else if (n_max <= 2048)
@@ -189,11 +214,8 @@ int launch_fused_hg(const ScoreArgs& a, int k, int32_t* topk_idx, float* topk_sc
   constexpr int NW = EC > 32 ? 8 : kFusedWaves;
   constexpr int E = ((EC * 4 + NW - 1) / NW + 3) / 4 * 4;
   const size_t sh = (size_t)NW * kNBuf * TileGeom<KDT>::kBufBytes + (size_t)a.m * a.B * 4;
-  auto kern = k_refine_fused<HG, KDT, NW, kNBuf, E>;
-  // more than 64 KB of LDS per workgroup has to be asked for explicitly
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh) != hipSuccess)
-    return HISA_ERR_LAUNCH;
+  constexpr auto kern = k_refine_fused<HG, KDT, NW, kNBuf, E>;
+  if (raise_lds_limit<kern>(sh)) return HISA_ERR_LAUNCH;
   hipLaunchKernelGGL(kern, dim3(a.t_count), dim3(NW * 64), sh, st, a, k, topk_idx, topk_scores,
                      (const void*)nullptr, (int32_t*)nullptr, 0);
   return HISA_OK;
@@ -216,10 +238,8 @@ int launch_indexer_hg(const ScoreArgs& a, const void* pooled, int k, int32_t* bl
   const int sc_floats = (int)round_up(a.m * a.B > M ? a.m * a.B : M, 32);
   const size_t tile = TileGeom<KDT>::kBufBytes < 8192 ? 8192 : TileGeom<KDT>::kBufBytes;
   const size_t sh = (size_t)NW * kNBuf * tile + (size_t)sc_floats * 4 + (size_t)round_up(a.m, 4) * 4;
-  auto kern = k_refine_fused<HG, KDT, NW, kNBuf, E, E1>;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)sh) != hipSuccess)
-    return HISA_ERR_LAUNCH;
+  constexpr auto kern = k_refine_fused<HG, KDT, NW, kNBuf, E, E1>;
+  if (raise_lds_limit<kern>(sh)) return HISA_ERR_LAUNCH;
   hipLaunchKernelGGL(kern, dim3(a.t_count), dim3(NW * 64), sh, st, a, k, topk_idx, topk_scores, pooled,
                      block_idx_out, sc_floats);
   return HISA_OK;
@@ -370,7 +390,8 @@ int hisa_block_sparse_tokens(const hisa_queries* queries, const hisa_keys* keys,
   a.m = m;
   a.B = B;
   const int gx = (m * B + 255) / 256;
-  hipLaunchKernelGGL(k_block_sparse_tokens, dim3(gx > 16 ? 16 : gx, queries->T), dim3(256), 0,
+  a.groups = gx > 16 ? 16 : gx;
+  hipLaunchKernelGGL(k_block_sparse_tokens, dim3((unsigned)((long)a.groups * queries->T)), dim3(256), 0,
                      (hipStream_t)stream, a, tokens);
   return launch_status();
 }
@@ -466,10 +487,10 @@ int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, co
   return launch_status();
 }
 
-int hisa_token_refine_topk(const hisa_queries* queries, const hisa_keys* keys, int32_t B, int32_t m,
-                           const int32_t* block_idx, int32_t k, int32_t* topk_idx,
-                           float* topk_scores, float* cand_scores, void* ws, size_t ws_bytes,
-                           void* stream) {
+static int token_refine_impl(const hisa_queries* queries, const hisa_keys* keys, int32_t B, int32_t m,
+                             const int32_t* block_idx, int32_t k, int32_t* topk_idx,
+                             float* topk_scores, float* cand_scores, void* ws, size_t ws_bytes,
+                             void* stream) {
   int st = check_queries(queries);
   if (st) return st;
   st = check_keys(keys, true);
@@ -531,6 +552,14 @@ int hisa_token_refine_topk(const hisa_queries* queries, const hisa_keys* keys, i
   return launch_status();
 }
 
+int hisa_token_refine_topk(const hisa_queries* queries, const hisa_keys* keys, int32_t B, int32_t m,
+                           const int32_t* block_idx, int32_t k, int32_t* topk_idx,
+                           float* topk_scores, float* cand_scores, void* ws, size_t ws_bytes,
+                           void* stream) {
+  return token_refine_impl(queries, keys, B, m, block_idx, k, topk_idx, topk_scores, cand_scores, ws, ws_bytes,
+                           stream);
+}
+
 int hisa_indexer_topk(const hisa_queries* queries, const hisa_keys* keys, const void* pooled,
                       int32_t pooled_dtype, int32_t B, int32_t m, int32_t k, int32_t* block_idx,
                       int32_t* topk_idx, float* topk_scores, void* stream) {
@@ -583,6 +612,11 @@ int dsa_flat_indexer_topk(const hisa_queries* queries, const hisa_keys* keys, in
   if (!ws) return HISA_ERR_WORKSPACE;
   long chunk = (long)(ws_bytes / (size_t)p.per_query);
   if (chunk > T) chunk = T;
+  {
+    // a chunk's scoring launch holds chunk * (workgroups per row) workgroups: keep it a legal grid
+    const long groups = path == PATH_F32 ? (keys->s_max + 1023L) / 1024 : (keys->s_max + 255L) / 256;
+    if (chunk > kMaxGrid / groups) chunk = kMaxGrid / groups;
+  }
   if (chunk >= 8) chunk = chunk / 8 * 8;
   if (chunk < 1 || (chunk < 8 && chunk < T)) return HISA_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
@@ -608,11 +642,8 @@ int dsa_flat_indexer_topk(const hisa_queries* queries, const hisa_keys* keys, in
     if (flat_streams(keys, k)) {
       sa.out_idx = topk_idx + t0 * k;
       sa.out_scores = topk_scores ? topk_scores + t0 * k : nullptr;
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(k_select_stream),
-                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                              StreamSelect::kBytes) != hipSuccess)
-        return HISA_ERR_LAUNCH;
-      hipLaunchKernelGGL(k_select_stream, dim3(1, tc), dim3(StreamSelect::kThreads), StreamSelect::kBytes, s, sa);
+      if (raise_lds_limit<k_select_stream>(StreamSelect::kBytes)) return HISA_ERR_LAUNCH;
+      hipLaunchKernelGGL(k_select_stream, dim3(tc), dim3(StreamSelect::kThreads), StreamSelect::kBytes, s, sa);
     } else if (p.n_seg == 1) {
       sa.out_idx = topk_idx + t0 * k;
       sa.out_scores = topk_scores ? topk_scores + t0 * k : nullptr;

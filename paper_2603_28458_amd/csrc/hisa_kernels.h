@@ -51,6 +51,7 @@ struct ScoreArgs {
   long ld;
   int t_begin, t_count;
   int tiles_per_wave;        // score_ranges: 32-key tiles each wave handles
+  int groups;                // score_ranges: workgroups per query (the grid holds t_count * groups)
 };
 
 // Position and sequence of query t, clamped so that no key row past the sequence is visible.
@@ -78,6 +79,19 @@ __device__ __forceinline__ int query_lo(const int32_t* q_lo, int t, int pos) {
   int lo = q_lo ? q_lo[t] : 0;
   lo = lo < 0 ? 0 : lo;
   return lo > pos + 1 ? pos + 1 : lo;
+}
+
+// Grids whose second dimension would be the query (row) index are launched one-dimensional, as
+// rows * gx workgroups with the gx workgroups of a row adjacent: the y dimension of a grid stops at
+// 65535, the x dimension at 2^31 - 1.
+struct RowGroup {
+  int row, x;
+};
+__device__ __forceinline__ RowGroup row_group(int gx) {
+  const int b = (int)blockIdx.x;
+  if (gx <= 1) return {b, 0};
+  const int row = b / gx;
+  return {row, b - row * gx};
 }
 
 // ------------------------------------------------------------------------------------------
@@ -194,13 +208,14 @@ __global__ __launch_bounds__(256) void k_pool_append(const void* __restrict__ ke
 
 // Block-Sparse baseline (Section 5): every visible token of the kept blocks.
 __global__ __launch_bounds__(256) void k_block_sparse_tokens(ScoreArgs a, int32_t* __restrict__ tokens) {
-  const int t = blockIdx.y;
+  const RowGroup rg = row_group(a.groups);
+  const int t = rg.row;
   int seq;
   const int pos = query_pos(a, t, seq);
   const int lo = query_lo(a.q_lo, t, pos);
   const int n_slots = a.m * a.B;
   const int n_blocks = (int)(a.rows_per_seq / a.B);
-  for (int c = blockIdx.x * 256 + threadIdx.x; c < n_slots; c += gridDim.x * 256) {
+  for (int c = rg.x * 256 + threadIdx.x; c < n_slots; c += a.groups * 256) {
     const int slot = c / a.B;
     const int blk = a.block_idx[(long)t * a.m + slot];
     const int tok = blk * a.B + (c - slot * a.B);
@@ -301,7 +316,8 @@ __global__ __launch_bounds__(256) void k_fill_f32(float* p, long n, float v) {
 // per (chunk of keys, query); the query's heads and gates sit in LDS, each thread scores one key.
 __global__ __launch_bounds__(256) void k_score_ranges_f32(ScoreArgs a, int keys_per_wg) {
   extern __shared__ float qs[];   // H*d query values, then H gates
-  const int t = a.t_begin + blockIdx.y;
+  const RowGroup rg = row_group(a.groups);
+  const int t = a.t_begin + rg.row;
   const int tid = threadIdx.x;
   int seq;
   const int pos = query_pos(a, t, seq);
@@ -314,10 +330,10 @@ __global__ __launch_bounds__(256) void k_score_ranges_f32(ScoreArgs a, int keys_
   const int n_total = gather ? a.m * a.B : visible_rows(a, pos);
   const int lo = query_lo(a.q_lo, t, pos);
   const int lo_row = lo / a.pos_div;   // first visible row when the rows are blocks or tokens in order
-  const int c0 = blockIdx.x * keys_per_wg;
+  const int c0 = rg.x * keys_per_wg;
   const int c1 = (c0 + keys_per_wg) < n_total ? (c0 + keys_per_wg) : n_total;
   const float* kbase = (const float*)a.keys + (long)seq * a.rows_per_seq * d;
-  float* out = a.out + (long)blockIdx.y * a.ld;
+  float* out = a.out + (long)rg.row * a.ld;
   for (int c = c0 + tid; c < c1; c += 256) {
     long row = c;
     bool valid = c >= lo_row;
@@ -509,7 +525,8 @@ template <int HG, int KDT>
 __global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
   constexpr int NB = 2;
   __shared__ __align__(16) unsigned char ring[4 * NB * TileGeom<KDT>::kBufBytes];
-  const int t = a.t_begin + blockIdx.y;
+  const RowGroup rg = row_group(a.groups);
+  const int t = a.t_begin + rg.row;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   int seq;
   const int pos = query_pos(a, t, seq);
@@ -518,12 +535,12 @@ __global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
   const int n_tiles = gather ? a.m * (a.B >> 5) : (n_vis + 31) >> 5;
   // first visible row: a token when gathering, else a row of the array in order (token or block)
   const int lo_row = gather ? query_lo(a.q_lo, t, pos) : query_lo(a.q_lo, t, pos) / a.pos_div;
-  const int v0 = blockIdx.x * 4 * a.tiles_per_wave;
+  const int v0 = rg.x * 4 * a.tiles_per_wave;
   if (v0 >= n_tiles) return;
   // in-order rows below the first visible one are neither scored nor written: the select starts
   // at the first visible row (rounded down to four)
   if (!gather && (v0 + 4 * a.tiles_per_wave) * 32 <= lo_row) return;
-  float* out = a.out + (long)blockIdx.y * a.ld;
+  float* out = a.out + (long)rg.row * a.ld;
   const int n_blocks = (int)(a.rows_per_seq / a.B);
 
   // the four waves share one query: its fragment is loaded (fp8 keys: converted) once, through
@@ -794,7 +811,8 @@ __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
   // decode step, with one workgroup per query, mostly waited for).
   constexpr bool kStaged = THREADS * E * 4 <= 32768;
   __shared__ __align__(16) uint32_t staged[kStaged ? THREADS * E : 4];
-  const int row = blockIdx.y, seg = blockIdx.x;
+  const RowGroup rg = row_group(a.n_seg);
+  const int row = rg.row, seg = rg.x;
   const int t = a.t_begin + row;
   const float* sc = a.scores + (long)row * a.ld;
   int n = a.n_fixed;
@@ -909,7 +927,7 @@ __global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(Sel
   uint32_t* bc = tot + 2 * NW;                                      // broadcast words
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int row = blockIdx.y;
+  const int row = blockIdx.x;
   const int t = a.t_begin + row;
   int sq = a.q_seq ? a.q_seq[t] : 0;
   sq = sq < 0 ? 0 : (sq >= a.n_seq ? a.n_seq - 1 : sq);

@@ -9,6 +9,9 @@ The HIP path and the oracle get the same stored bits.  Stage by stage:
             path when the shapes allow;
   flat      Eqs. 1-2 by the threshold rule.
 Sets are compared as sets; the GPU's rows must be ascending with -1 padding at the end.
+Every score comparison also asserts the regression bound of its arithmetic path (tests/util.py,
+DESIGN_RTOL: 1e-5 of the row maximum on the bf16 MFMA and fp32 paths, 3e-4 on the fp8 MFMA path),
+and every swap at a threshold must lie within twice that bound of the threshold.
 """
 from __future__ import annotations
 
@@ -17,7 +20,7 @@ import torch
 
 from oracle import hisa_oracle as O
 from paper_2603_28458_amd import hisa
-from tests.util import check_scores, check_set, oracle_args, rtol_for
+from tests.util import check_scores, check_set, design_rtol_for, oracle_args, rtol_for
 
 
 def _np(t):
@@ -61,6 +64,8 @@ def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, 
     """Runs the four entry points on `wl` and checks them on `queries` (all if None).
     Returns a dict of statistics (max relative score error, number of threshold swaps)."""
     rtol = rtol_for(wl)
+    d_tok = design_rtol_for(wl)                 # token keys: bf16 / fp8 / fp32 path
+    d_blk = design_rtol_for(wl, pooled=True)    # pooled keys: bf16 (or fp32) path
     Q, K = hisa.to_device(wl)
     pd_code = hisa.DTYPE_CODE[wl.pooled_dtype]
     qs = np.arange(wl.T) if queries is None else np.asarray(queries)
@@ -84,8 +89,8 @@ def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, 
     bi = _np(block_idx)
     o_bi, o_J = O.hisa_block_score_topk(**oracle_args(wl, keys=False), pooled=pooled_bits,
                                         pooled_dtype=wl.pooled_dtype, B=wl.B, m=wl.m, queries=qs)
-    stats["J_err"] = check_scores(_np(J)[qs], o_J, rtol, "block scores")
-    stats["block_swaps"] = _check_block_sets(wl, qs, bi, o_bi, o_J, rtol, "two-call")
+    stats["J_err"] = check_scores(_np(J)[qs], o_J, rtol, "block scores", d_blk)
+    stats["block_swaps"] = _check_block_sets(wl, qs, bi, o_bi, o_J, rtol, "two-call", d_blk)
 
     # ---- Stage 2 (Eqs. 7-9) on the GPU's block_idx: two-kernel path with candidate scores
     topk_idx, topk_sc, cand = hisa.hisa_token_refine_topk(Q, K, wl.B, wl.m, block_idx, wl.k,
@@ -93,10 +98,10 @@ def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, 
     torch.cuda.synchronize()
     o_ti, o_ts, o_cand = O.hisa_token_refine_topk(**oracle_args(wl), B=wl.B, m=wl.m, block_idx=bi[qs],
                                                   k=wl.k, queries=qs)
-    stats["cand_err"] = check_scores(_np(cand)[qs], o_cand, rtol, "candidate scores")
+    stats["cand_err"] = check_scores(_np(cand)[qs], o_cand, rtol, "candidate scores", d_tok)
     ti = _np(topk_idx)
     ts = _np(topk_sc)
-    stats["token_swaps"] = _check_token_sets(wl, qs, bi, ti, ts, o_ti, o_cand, rtol, "two-kernel")
+    stats["token_swaps"] = _check_token_sets(wl, qs, bi, ti, ts, o_ti, o_cand, rtol, "two-kernel", d_tok)
 
     # ---- Stage 2 fused path (taken by the library when cand_scores is not requested)
     if fused is None:
@@ -106,7 +111,7 @@ def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, 
         f_idx2, _, _ = hisa.hisa_token_refine_topk(Q, K, wl.B, wl.m, block_idx, wl.k)
         torch.cuda.synchronize()
         assert torch.equal(f_idx, f_idx2)
-        stats["fused_swaps"] = _check_token_sets(wl, qs, bi, _np(f_idx), _np(f_sc), o_ti, o_cand, rtol, "fused")
+        stats["fused_swaps"] = _check_token_sets(wl, qs, bi, _np(f_idx), _np(f_sc), o_ti, o_cand, rtol, "fused", d_tok)
         # same fp32 scores, same rule: the two GPU paths must agree exactly
         assert torch.equal(f_idx, topk_idx), "fused and two-kernel Stage 2 select different sets"
     else:
@@ -124,25 +129,30 @@ def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, 
         torch.cuda.synchronize()
         assert torch.equal(a_ti, a_ti2)
         abi = _np(a_bi)
-        stats["single_block_swaps"] = _check_block_sets(wl, qs, abi, o_bi, o_J, rtol, "single-launch")
+        stats["single_block_swaps"] = _check_block_sets(wl, qs, abi, o_bi, o_J, rtol, "single-launch", d_blk)
         if np.array_equal(abi[qs], bi[qs]):
             s_ti, s_cand = o_ti, o_cand
         else:   # a legal Stage 1 swap: Stage 2 is judged on the block ids this launch kept
             s_ti, _, s_cand = O.hisa_token_refine_topk(**oracle_args(wl), B=wl.B, m=wl.m, block_idx=abi[qs],
                                                        k=wl.k, queries=qs)
         stats["single_token_swaps"] = _check_token_sets(wl, qs, abi, _np(a_ti), _np(a_ts), s_ti, s_cand, rtol,
-                                                        "single-launch")
+                                                        "single-launch", d_tok)
 
     # ---- end to end: where the GPU's block set equals the oracle's own, the token set follows it
-    o_full = O.hisa_indexer(**oracle_args(wl), seq_len=wl.seq_len, B=wl.B, m=wl.m, k=wl.k,
-                            pooled_dtype=wl.pooled_dtype, queries=qs, pooled=want)
-    same = [i for i in range(qs.size) if np.array_equal(o_full["block_idx"][i], bi[qs[i]])]
+    if np.array_equal(pooled_bits, want):
+        # the GPU's pooled cache is bit-identical to the oracle's: the oracle's own Stage 1 is o_bi, and
+        # its own Stage 2 on a query whose GPU block set equals o_bi is the o_ti / o_cand computed above
+        e_bi, e_ti, e_cand = o_bi, o_ti, o_cand
+    else:
+        o_full = O.hisa_indexer(**oracle_args(wl), seq_len=wl.seq_len, B=wl.B, m=wl.m, k=wl.k,
+                                pooled_dtype=wl.pooled_dtype, queries=qs, pooled=want)
+        e_bi, e_ti, e_cand = o_full["block_idx"], o_full["topk_idx"], o_full["cand_scores"]
+    same = [i for i in range(qs.size) if np.array_equal(e_bi[i], bi[qs[i]])]
     stats["same_block_sets"] = len(same) / max(1, qs.size)
     lo = _lo(wl)
     for i in same:
-        toks, sc = _cand_of(wl, bi[qs[i]][bi[qs[i]] >= 0].astype(np.int64), pos[qs[i]], lo[qs[i]],
-                            o_full["cand_scores"][i])
-        check_set(ti[qs[i]], o_full["topk_idx"][i], toks, sc, rtol, f"end-to-end set of query {qs[i]}")
+        toks, sc = _cand_of(wl, bi[qs[i]][bi[qs[i]] >= 0].astype(np.int64), pos[qs[i]], lo[qs[i]], e_cand[i])
+        check_set(ti[qs[i]], e_ti[i], toks, sc, rtol, f"end-to-end set of query {qs[i]}", d_tok)
 
     # ---- flat DSA (Eqs. 1-2)
     if check_flat:
@@ -154,9 +164,16 @@ def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, 
         swaps = 0
         for i, t in enumerate(fq):
             ids = lo[t] + np.arange(rows[i].size)         # the row covers the positions lo .. pos
-            swaps += check_set(fi[t], o_fi[i], ids, rows[i], rtol, f"flat set of query {t}")
+            swaps += check_set(fi[t], o_fi[i], ids, rows[i], rtol, f"flat set of query {t}", d_tok)
             nv = int((fi[t] >= 0).sum())
+            # the bound is relative to the largest score of the whole row, as for the candidate scores
+            A_row = np.abs(rows[i]).max() if rows[i].size else 0.0
+            err = np.abs(fs[t, :nv].astype(np.float64) - rows[i][fi[t, :nv] - lo[t]])
             check_scores(fs[t, :nv][None], rows[i][fi[t, :nv] - lo[t]][None], rtol, f"flat scores of query {t}")
+            if nv and A_row > 0:
+                assert err.max() <= d_tok * A_row, (f"flat scores of query {t}: error {err.max() / A_row:.3g} x the row "
+                                                    f"maximum exceeds the regression bound {d_tok:.3g}")
+                stats["flat_err"] = max(stats.get("flat_err", 0.0), float(err.max() / A_row))
             assert np.all(np.isneginf(fs[t, nv:]))
         stats["flat_swaps"] = swaps
         stats["iou_hisa_flat"] = float(np.mean([O.iou(ti[t], fi[t]) for t in qs]))
@@ -165,7 +182,7 @@ def run_and_check(wl, queries=None, check_flat=True, fused=None, verbose=False, 
     return stats
 
 
-def _check_block_sets(wl, qs, bi, o_bi, o_J, rtol, what):
+def _check_block_sets(wl, qs, bi, o_bi, o_J, rtol, what, design_rtol=None):
     """Eq. 6 with the forced blocks: shape rules, then the threshold rule on the free slots."""
     pos = wl.positions()
     lo = _lo(wl)
@@ -185,25 +202,30 @@ def _check_block_sets(wl, qs, bi, o_bi, o_J, rtol, what):
             # the forced blocks never take part in a swap: compare the free slots
             ov = o_bi[i][o_bi[i] >= 0]
             swaps += check_set(v[1:-1], ov[1:-1], np.arange(b_0 + 1, b_t), o_J[i, b_0 + 1:b_t], rtol,
-                               f"{what} block set of query {t}")
+                               f"{what} block set of query {t}", design_rtol)
         else:
             assert np.array_equal(v, np.arange(b_0, b_t + 1))
             assert np.all(row[v.size:] == -1)
     return swaps
 
 
-def _check_token_sets(wl, qs, bi, ti, ts, o_ti, o_cand, rtol, what):
+def _check_token_sets(wl, qs, bi, ti, ts, o_ti, o_cand, rtol, what, design_rtol=None):
     pos = wl.positions()
     lo = _lo(wl)
     swaps = 0
     for i, t in enumerate(qs):
         C = bi[t][bi[t] >= 0].astype(np.int64)
         toks, sc = _cand_of(wl, C, pos[t], lo[t], o_cand[i])
-        swaps += check_set(ti[t], o_ti[i], toks, sc, rtol, f"{what} token set of query {t}")
+        swaps += check_set(ti[t], o_ti[i], toks, sc, rtol, f"{what} token set of query {t}", design_rtol)
         nv = int((ti[t] >= 0).sum())
         assert nv == min(wl.k, toks.size)
         if ts is not None:
             want = sc[np.searchsorted(toks, ti[t, :nv])]
             check_scores(ts[t, :nv][None], want[None], rtol, f"{what} top-k scores of query {t}")
+            if design_rtol is not None and nv:
+                A_row = np.abs(sc).max()     # relative to the largest candidate score, as for cand_scores
+                err = np.abs(ts[t, :nv].astype(np.float64) - want).max()
+                assert err <= design_rtol * A_row, (f"{what} top-k scores of query {t}: error {err / A_row:.3g} x the "
+                                                    f"row maximum exceeds the regression bound {design_rtol:.3g}")
             assert np.all(np.isneginf(ts[t, nv:]))
     return swaps

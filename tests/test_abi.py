@@ -78,6 +78,25 @@ def test_host_side_validation_rejects_before_launch(lib):
     assert lib.dsa_flat_indexer_topk(C.byref(q3), C.byref(k), 64, fake, None, fake, 1 << 30, None) == 6
 
 
+def test_query_and_sequence_counts_beyond_the_launch_limits_are_refused(lib):
+    """T <= 4194304 and n_seq <= 65535 (header, "Supported shapes"): every entry point that takes
+    queries returns HISA_ERR_SHAPE on the host, before any kernel of the call is enqueued."""
+    fake = 0x1000
+    big = (1 << 22) + 1
+    q, k = _structs(T=big, s_max=65536)
+    ok_q, _ = _structs(T=1 << 22, s_max=65536)
+    huge = 1 << 40
+    assert lib.hisa_block_score_topk(C.byref(q), C.byref(k), fake, 1, 128, 64, fake, None, fake, huge, None) == 2
+    assert lib.hisa_token_refine_topk(C.byref(q), C.byref(k), 128, 64, fake, 2048, fake, None, None, fake, huge, None) == 2
+    assert lib.hisa_indexer_topk(C.byref(q), C.byref(k), fake, 1, 128, 64, 2048, None, fake, None, None) == 2
+    assert lib.dsa_flat_indexer_topk(C.byref(q), C.byref(k), 2048, fake, None, fake, huge, None) == 2
+    # the limit itself passes this check (and fails a later one here: the workspace is too small)
+    assert lib.hisa_block_score_topk(C.byref(ok_q), C.byref(k), fake, 1, 128, 64, fake, None, fake, 16, None) == 5
+    q2, k2 = _structs(n_seq=65536)
+    assert lib.hisa_pool_blocks(C.byref(k2), 128, 0, 8, fake, 1, None) == 2
+    assert lib.dsa_flat_indexer_topk(C.byref(q2), C.byref(k2), 64, fake, None, fake, 1 << 30, None) == 2
+
+
 def test_validation_of_the_auxiliary_entry_points(lib):
     fake = 0x1000
     q, k = _structs()

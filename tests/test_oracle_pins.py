@@ -163,6 +163,9 @@ def test_hand_worked_example():
         assert bi[bi >= 0].tolist() == c["blocks"], c
         ti = r["topk_idx"][0]
         assert ti[ti >= 0].tolist() == c["hisa"], c
+        # Eq. 8 in the slot layout of the candidate-score output (kept block rank * B + offset)
+        want_cand = [-np.inf if v == "-inf" else float(v) for v in c["cand_scores"]]
+        assert r["cand_scores"][0].tolist() == want_cand, c
         fi, _ = O.dsa_flat_indexer_topk(q=q, q_dtype="f32", w=w, q_seq=None, q_pos=pos, keys=keys, k_dtype="f32",
                                         k_scale=None, k=c["k"])
         assert fi[0][fi[0] >= 0].tolist() == c["flat"], c
