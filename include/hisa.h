@@ -153,6 +153,26 @@ int hisa_token_refine_topk(const hisa_queries* queries, const hisa_keys* keys, i
                            void* stream);
 
 /*
+ * hisa_token_refine_topk for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same inputs, outputs and results as hisa_token_refine_topk with cand_scores == NULL; the
+ * candidate scores of the two-kernel path (T < 256, or m * B > 16384) go through a static device
+ * array of HISA_STATIC_SCRATCH_BYTES inside the library instead of a workspace.  The call
+ * allocates and frees nothing and, like every other call, only enqueues kernels on `stream`.
+ *   - Limit: T * m * B * 4 <= HISA_STATIC_SCRATCH_BYTES on that path (a decode batch of 512
+ *     queries at m * B = 8192); beyond it the call returns HISA_ERR_WORKSPACE and launches nothing.
+ *   - Every GPU the process uses holds its own copy of the array until the process ends.  The
+ *     first call on a device looks its address up (make that call outside a graph capture).
+ *   - All calls on one GPU share the array: calls that may overlap in time (different streams
+ *     without an ordering between them) race on it.  Nothing in it has to be cleared between calls:
+ *     the scoring kernel rewrites every slot the select reads.
+ */
+#define HISA_STATIC_SCRATCH_BYTES (16u << 20)
+int hisa_token_refine_topk_static(const hisa_queries* queries, const hisa_keys* keys, int32_t B, int32_t m,
+                                  const int32_t* block_idx, int32_t k, int32_t* topk_idx,
+                                  float* topk_scores, void* stream);
+
+/*
  * Flat DSA indexer (Eqs. 1-2): scores every visible key s <= q_pos and selects the k best.
  * Same outputs as Stage 2.  The scores of a chunk of queries go through the workspace (one row of
  * round_up(s_max, 64) floats per query) and are selected row by row; the library loops over

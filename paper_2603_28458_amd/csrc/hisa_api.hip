@@ -487,10 +487,29 @@ int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, co
   return launch_status();
 }
 
+// ---- Stage 2 for callers that cannot allocate ---------------------------------------------
+// The candidate scores of the two-kernel path go through this array instead of a caller workspace.
+// Every GPU the library runs on holds its own copy, at its own address, until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t)HISA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+
+// Device address of `scratch` on the current device (in host code the array's name is only a
+// handle for the symbol, not an address a kernel can use), looked up once per device.
+static void* static_scratch_ptr() {
+  static std::atomic<void*> ptrs[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = ptrs[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+  ptrs[dev].store(p, std::memory_order_release);
+  return p;
+}
+
 static int token_refine_impl(const hisa_queries* queries, const hisa_keys* keys, int32_t B, int32_t m,
                              const int32_t* block_idx, int32_t k, int32_t* topk_idx,
                              float* topk_scores, float* cand_scores, void* ws, size_t ws_bytes,
-                             void* stream) {
+                             bool static_ws, void* stream) {
   int st = check_queries(queries);
   if (st) return st;
   st = check_keys(keys, true);
@@ -530,6 +549,13 @@ static int token_refine_impl(const hisa_queries* queries, const hisa_keys* keys,
 
   float* C = cand_scores;
   if (!C) {
+    if (static_ws) {
+      // every argument has passed validation; only now is the device asked for the array's address
+      if ((size_t)T * n_slots * 4 > kStaticScratchBytes) return HISA_ERR_WORKSPACE;
+      ws = static_scratch_ptr();
+      if (!ws) return HISA_ERR_LAUNCH;
+      ws_bytes = kStaticScratchBytes;
+    }
     if (!ws || ws_bytes < (size_t)T * n_slots * 4) return HISA_ERR_WORKSPACE;
     C = (float*)ws;
   }
@@ -557,6 +583,13 @@ int hisa_token_refine_topk(const hisa_queries* queries, const hisa_keys* keys, i
                            float* topk_scores, float* cand_scores, void* ws, size_t ws_bytes,
                            void* stream) {
   return token_refine_impl(queries, keys, B, m, block_idx, k, topk_idx, topk_scores, cand_scores, ws, ws_bytes,
+                           false, stream);
+}
+
+int hisa_token_refine_topk_static(const hisa_queries* queries, const hisa_keys* keys, int32_t B, int32_t m,
+                                  const int32_t* block_idx, int32_t k, int32_t* topk_idx,
+                                  float* topk_scores, void* stream) {
+  return token_refine_impl(queries, keys, B, m, block_idx, k, topk_idx, topk_scores, nullptr, nullptr, 0, true,
                            stream);
 }
 

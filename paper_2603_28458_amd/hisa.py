@@ -20,7 +20,9 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libh
 
 EXPORTS = ["hisa_pool_blocks", "hisa_pool_append", "hisa_block_score_topk", "hisa_token_refine_topk",
            "hisa_block_sparse_tokens", "hisa_index_iou", "dsa_flat_indexer_topk", "hisa_workspace_bytes",
-           "hisa_status_string", "hisa_version", "hisa_probe_copy", "hisa_probe_mfma", "hisa_probe_mfma_fp8", "hisa_indexer_topk", "hisa_pool_blocks_max"]
+           "hisa_status_string", "hisa_version", "hisa_probe_copy", "hisa_probe_mfma", "hisa_probe_mfma_fp8", "hisa_indexer_topk", "hisa_pool_blocks_max",
+           "hisa_token_refine_topk_static"]
+STATIC_SCRATCH_BYTES = 16 << 20
 
 
 class HisaError(RuntimeError):
@@ -68,6 +70,9 @@ def lib() -> C.CDLL:
         L.hisa_token_refine_topk.argtypes = [C.POINTER(_Queries), C.POINTER(_Keys), i32, i32, vp, i32,
                                              vp, vp, vp, vp, sz, vp]
         L.hisa_token_refine_topk.restype = C.c_int
+        L.hisa_token_refine_topk_static.argtypes = [C.POINTER(_Queries), C.POINTER(_Keys), i32, i32, vp, i32,
+                                                    vp, vp, vp]
+        L.hisa_token_refine_topk_static.restype = C.c_int
         L.dsa_flat_indexer_topk.argtypes = [C.POINTER(_Queries), C.POINTER(_Keys), i32, vp, vp, vp,
                                             sz, vp]
         L.dsa_flat_indexer_topk.restype = C.c_int
@@ -277,6 +282,18 @@ def hisa_token_refine_topk(queries: Queries, keys: Keys, B: int, m: int, block_i
                                       0 if ws is None else ws.numel(), _stream(stream))
     _check(st, "hisa_token_refine_topk")
     return topk_idx, topk_scores, cand_scores
+
+
+def hisa_token_refine_topk_static(queries: Queries, keys: Keys, B: int, m: int, block_idx: torch.Tensor, k: int,
+                                  topk_idx: torch.Tensor, topk_scores: Optional[torch.Tensor] = None,
+                                  stream=None):
+    """Stage 2 (Eqs. 7-9) through the library's static scratch array: nothing is allocated, here or
+    in the library, so the outputs must be passed in.  Returns (topk_idx, topk_scores)."""
+    qc, kc = queries.c(), keys.c()
+    st = lib().hisa_token_refine_topk_static(C.byref(qc), C.byref(kc), B, m, _ptr(block_idx), k, _ptr(topk_idx),
+                                             _ptr(topk_scores), _stream(stream))
+    _check(st, "hisa_token_refine_topk_static")
+    return topk_idx, topk_scores
 
 
 def dsa_flat_indexer_topk(queries: Queries, keys: Keys, k: int, topk_idx: Optional[torch.Tensor] = None,

@@ -88,6 +88,7 @@ def test_query_and_sequence_counts_beyond_the_launch_limits_are_refused(lib):
     huge = 1 << 40
     assert lib.hisa_block_score_topk(C.byref(q), C.byref(k), fake, 1, 128, 64, fake, None, fake, huge, None) == 2
     assert lib.hisa_token_refine_topk(C.byref(q), C.byref(k), 128, 64, fake, 2048, fake, None, None, fake, huge, None) == 2
+    assert lib.hisa_token_refine_topk_static(C.byref(q), C.byref(k), 128, 64, fake, 2048, fake, None, None) == 2
     assert lib.hisa_indexer_topk(C.byref(q), C.byref(k), fake, 1, 128, 64, 2048, None, fake, None, None) == 2
     assert lib.dsa_flat_indexer_topk(C.byref(q), C.byref(k), 2048, fake, None, fake, huge, None) == 2
     # the limit itself passes this check (and fails a later one here: the workspace is too small)
@@ -95,6 +96,22 @@ def test_query_and_sequence_counts_beyond_the_launch_limits_are_refused(lib):
     q2, k2 = _structs(n_seq=65536)
     assert lib.hisa_pool_blocks(C.byref(k2), 128, 0, 8, fake, 1, None) == 2
     assert lib.dsa_flat_indexer_topk(C.byref(q2), C.byref(k2), 64, fake, None, fake, 1 << 30, None) == 2
+
+
+def test_static_scratch_call_validates_like_the_workspace_call(lib):
+    fake = 0x1000
+    q, k = _structs(T=8)
+    # hisa_token_refine_topk_static(queries, keys, B, m, block_idx, k, topk_idx, topk_scores, stream)
+    assert lib.hisa_token_refine_topk_static(None, C.byref(k), 128, 8, fake, 512, fake, None, None) == 1
+    assert lib.hisa_token_refine_topk_static(C.byref(q), C.byref(k), 128, 8, None, 512, fake, None, None) == 1
+    assert lib.hisa_token_refine_topk_static(C.byref(q), C.byref(k), 128, 4, fake, 2048, fake, None, None) == 4
+    assert lib.hisa_token_refine_topk_static(C.byref(q), C.byref(k), 48, 16, fake, 512, fake, None, None) == 2
+    # more candidate scores than the static array holds (200 x 65536 x 4 B > 16 MiB): refused
+    q2, k2 = _structs(T=200, s_max=131072)
+    assert lib.hisa_token_refine_topk_static(C.byref(q2), C.byref(k2), 128, 512, fake, 512, fake, None, None) == 5
+    assert hisa.STATIC_SCRATCH_BYTES == 16 << 20
+    header = open(os.path.join(ROOT, "include", "hisa.h")).read()
+    assert "#define HISA_STATIC_SCRATCH_BYTES (16u << 20)" in header
 
 
 def test_validation_of_the_auxiliary_entry_points(lib):

@@ -78,6 +78,9 @@ def _run_all(wl, single_launch):
     hisa.hisa_token_refine_topk(Q, K, B, m, block_idx, k, topk_idx=_guard(G, "topk_idx (cand path)", i32, (T, k), dev),
                                 topk_scores=_guard(G, "topk_scores (cand path)", f32, (T, k), dev),
                                 cand_scores=_guard(G, "cand_scores", f32, (T, m * B), dev))
+    if T * m * B * 4 <= hisa.STATIC_SCRATCH_BYTES or T >= 256:
+        hisa.hisa_token_refine_topk_static(Q, K, B, m, block_idx, k, _guard(G, "topk_idx (static)", i32, (T, k), dev),
+                                           _guard(G, "topk_scores (static)", f32, (T, k), dev))
     if single_launch:
         hisa.hisa_indexer_topk(Q, K, pooled, pd, B, m, k, block_idx=_guard(G, "block_idx (single launch)", i32, (T, m), dev),
                                topk_idx=_guard(G, "topk_idx (single launch)", i32, (T, k), dev),
