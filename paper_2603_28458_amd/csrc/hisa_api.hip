@@ -205,7 +205,7 @@ SelectArgs select_base(const hisa_queries* q, const hisa_keys* k) {
 }
 
 // Fused Stage 2: kFusedWaves waves per query; EC = candidates per thread of a 256-thread select
-// (32: up to 8192 candidates, 64: up to 16384); with 8 waves the per-thread count halves.
+// (16: up to 4096 candidates, 32: up to 8192, 64: up to 16384); with 8 waves the per-thread count halves.
 template <int HG, int KDT, int EC>
 int launch_fused_hg(const ScoreArgs& a, int k, int32_t* topk_idx, float* topk_scores,
                     hipStream_t st) {
@@ -213,7 +213,8 @@ int launch_fused_hg(const ScoreArgs& a, int k, int32_t* topk_idx, float* topk_sc
   // that one gets 8 waves (two per SIMD; and 32 instead of 64 candidates per thread in the select)
   constexpr int NW = EC > 32 ? 8 : kFusedWaves;
   constexpr int E = ((EC * 4 + NW - 1) / NW + 3) / 4 * 4;
-  const size_t sh = (size_t)NW * kNBuf * TileGeom<KDT>::kBufBytes + (size_t)a.m * a.B * 4;
+  const size_t sh = (size_t)NW * kNBuf * TileGeom<KDT>::kBufBytes + (size_t)a.m * a.B * 4 +
+                    sizeof(FineSelSmem<NW * 64, E>);
   constexpr auto kern = k_refine_fused<HG, KDT, NW, kNBuf, E>;
   if (raise_lds_limit<kern>(sh)) return HISA_ERR_LAUNCH;
   hipLaunchKernelGGL(kern, dim3(a.t_count), dim3(NW * 64), sh, st, a, k, topk_idx, topk_scores,
@@ -237,7 +238,8 @@ int launch_indexer_hg(const ScoreArgs& a, const void* pooled, int k, int32_t* bl
   const int M = (int)(a.rows_per_seq / a.B);
   const int sc_floats = (int)round_up(a.m * a.B > M ? a.m * a.B : M, 32);
   const size_t tile = TileGeom<KDT>::kBufBytes < 8192 ? 8192 : TileGeom<KDT>::kBufBytes;
-  const size_t sh = (size_t)NW * kNBuf * tile + (size_t)sc_floats * 4 + (size_t)round_up(a.m, 4) * 4;
+  const size_t sh = (size_t)NW * kNBuf * tile + (size_t)sc_floats * 4 + (size_t)round_up(a.m, 4) * 4 +
+                    sizeof(FineSelSmem<NW * 64, E>);
   constexpr auto kern = k_refine_fused<HG, KDT, NW, kNBuf, E, E1>;
   if (raise_lds_limit<kern>(sh)) return HISA_ERR_LAUNCH;
   hipLaunchKernelGGL(kern, dim3(a.t_count), dim3(NW * 64), sh, st, a, k, topk_idx, topk_scores, pooled,
@@ -296,6 +298,7 @@ const char* hisa_status_string(int status) {
 }
 
 const char* hisa_version(void) { return "0.1"; }
+
 
 static int pool_blocks_impl(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_t blk_end,
                             void* pooled, int32_t pooled_dtype, bool max_pool, void* stream) {
@@ -452,17 +455,17 @@ int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, co
   if (!path) return st;
   if (pooled_dtype != HISA_F32 && pooled_dtype != HISA_BF16) return HISA_ERR_DTYPE;
   const int T = queries->T;
-  float* J = block_scores;
-  if (!J) {
-    if (!ws || ws_bytes < (size_t)T * M * 4) return HISA_ERR_WORKSPACE;
-    J = (float*)ws;
-  }
   hipStream_t s = (hipStream_t)stream;
   ScoreArgs a = base_args(queries, keys);
   a.keys = pooled;
   a.k_scale = nullptr;
   a.rows_per_seq = M;
   a.pos_div = B;
+  float* J = block_scores;
+  if (!J) {
+    if (!ws || ws_bytes < (size_t)T * M * 4) return HISA_ERR_WORKSPACE;
+    J = (float*)ws;
+  }
   a.out = J;
   a.ld = M;
   a.t_begin = 0;
@@ -537,7 +540,10 @@ static int token_refine_impl(const hisa_queries* queries, const hisa_keys* keys,
   if (fused) {
     a.out = nullptr;
     const bool bf = keys->k_dtype == HISA_BF16;
-    if (n_slots <= 8192)
+    if (n_slots <= 4096)       // half the candidates: half as many per thread in the top-k
+      st = bf ? launch_fused<DT_BF16, 16>(a, k, topk_idx, topk_scores, s)
+              : launch_fused<DT_FP8, 16>(a, k, topk_idx, topk_scores, s);
+    else if (n_slots <= 8192)
       st = bf ? launch_fused<DT_BF16, 32>(a, k, topk_idx, topk_scores, s)
               : launch_fused<DT_FP8, 32>(a, k, topk_idx, topk_scores, s);
     else

@@ -18,6 +18,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace hisa {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -191,6 +193,93 @@ __device__ __forceinline__ u32x32 lds_read_tile_raw(uint32_t tile_addr) {
     kv[4 * kk + 3] = xs[kk][3];
   }
   return kv;
+}
+
+// The same eight reads WITHOUT the wait: the caller waits per chunk (tile_chunk_ready) right before
+// the MFMAs that consume it, so the first MFMAs start as soon as the first chunk has arrived.  LDS
+// operations complete in order, so "at most 7 - kk operations outstanding" implies that chunk kk is
+// there, whatever else (score writes, scale reads) was issued behind the eight reads.
+struct TileRegs {
+  u32x4e x[8];
+};
+
+__device__ __forceinline__ void lds_read_tile_issue(uint32_t tile_addr, TileRegs& t) {
+  const int lane = lane_id();
+  const int half = lane >> 5;
+  const int r = lane & 31;
+  uint32_t ad[8];
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk)
+    ad[kk] = tile_addr + (uint32_t)((r * 16 + ((2 * kk + half) ^ (r & 15))) << 4);
+  asm volatile(
+      "ds_read_b128 %0, %8\n\t"
+      "ds_read_b128 %1, %9\n\t"
+      "ds_read_b128 %2, %10\n\t"
+      "ds_read_b128 %3, %11\n\t"
+      "ds_read_b128 %4, %12\n\t"
+      "ds_read_b128 %5, %13\n\t"
+      "ds_read_b128 %6, %14\n\t"
+      "ds_read_b128 %7, %15"
+      : "=&v"(t.x[0]), "=&v"(t.x[1]), "=&v"(t.x[2]), "=&v"(t.x[3]), "=&v"(t.x[4]), "=&v"(t.x[5]), "=&v"(t.x[6]),
+        "=&v"(t.x[7])
+      : "v"(ad[0]), "v"(ad[1]), "v"(ad[2]), "v"(ad[3]), "v"(ad[4]), "v"(ad[5]), "v"(ad[6]), "v"(ad[7])
+      : "memory");
+}
+
+template <int LEFT>
+__device__ __forceinline__ void tile_chunk_ready(u32x4e& x) {
+  asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(LEFT));
+}
+
+// after_reads(): called once every read has left the LDS tile (from then on the tile may be
+// overwritten), behind the MFMAs of the first two chunks, whose 128 cycles cover the rest of the reads.
+template <int HG, bool EVERY_CHUNK = false, class AfterReads>
+__device__ __forceinline__ accvec<HG> mfma_tile_progressive(const QFrag<HG>& f, TileRegs& t, AfterReads after_reads) {
+  f32x16 acc[HG];
+#pragma unroll
+  for (int g = 0; g < HG; ++g)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[g][i] = 0.f;
+  auto chunk = [&](int kk) {
+    const bf16x8 b = as_bf16x8(make_uint4(t.x[kk][0], t.x[kk][1], t.x[kk][2], t.x[kk][3]));
+#pragma unroll
+    for (int g = 0; g < HG; ++g)
+      acc[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[g][kk], b, acc[g], 0, 0, 0);
+  };
+  tile_chunk_ready<7>(t.x[0]);
+  chunk(0);
+  tile_chunk_ready<6>(t.x[1]);
+  chunk(1);
+  if constexpr (EVERY_CHUNK) {
+    // nothing waits for the tile to be free: every chunk is awaited right before its own MFMAs
+    tile_chunk_ready<5>(t.x[2]);
+    chunk(2);
+    tile_chunk_ready<4>(t.x[3]);
+    chunk(3);
+    tile_chunk_ready<3>(t.x[4]);
+    chunk(4);
+    tile_chunk_ready<2>(t.x[5]);
+    chunk(5);
+    tile_chunk_ready<1>(t.x[6]);
+    chunk(6);
+    tile_chunk_ready<0>(t.x[7]);
+    chunk(7);
+    after_reads();
+  } else {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(t.x[2]), "+v"(t.x[3]), "+v"(t.x[4]), "+v"(t.x[5]), "+v"(t.x[6]), "+v"(t.x[7])
+                 :
+                 : "memory");
+    after_reads();
+#pragma unroll
+    for (int kk = 2; kk < 8; ++kk) chunk(kk);
+  }
+  accvec<HG> out;
+#pragma unroll
+  for (int g = 0; g < HG; ++g)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) out[g * 16 + i] = acc[g][i];
+  return out;
 }
 
 template <int HG>
@@ -952,6 +1041,230 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
     e_run += eq;
   }
   return n_valid < k ? n_valid : k;
+}
+
+// ------------------------------------------------------------------------------------------
+// Fast path of the top-k behind the fused Stage 2 scoring: ONE histogram pass with bins fine enough
+// (2048 over the row's own score range) that the bin holding the k-th score has a handful of
+// entries, whose k-th is then found by counting.  The threshold tau is a score of the row, and the
+// path emits only after it has CHECKED that exactly k scores are >= tau: then those k are the top
+// k whatever the binning did (ties at tau are either all in or the check fails).  On any doubt -- a
+// crowded bin, the k-th among the masked entries, ties across the threshold, a count that does not
+// come out -- it returns false BEFORE writing anything, and the caller runs select_topk.
+// Its scratch is NOT shared with anything else in the kernel, so that the bins can be zeroed at
+// kernel start and the row's score range can be collected by the scoring waves as they go: the
+// select itself then needs five workgroup barriers (the general select: about sixteen).
+//   fine_select_prepare      at kernel start, every thread;
+//   fine_select_range        after a wave's last score, every lane (x_max / x_min: the largest and
+//                            smallest score the lane has produced, NaN entries ignored), BEFORE the
+//                            barrier that ends scoring;
+//   select_topk_fine         after that barrier, every thread.  vals(q) -> the scores of elements
+//                            4q .. 4q+3 as stored (NaN: not a candidate); thread t owns the E
+//                            consecutive elements from t*E; emit(pos, v, tau, dump): the thread's
+//                            selected elements are those with v[j] >= tau, the first of them is the
+//                            pos-th selected of the row (ascending element index); dump is an LDS
+//                            word of the thread's own that may be overwritten.
+template <int NT, int E>
+struct FineSelSmem {
+  static constexpr int NBIN = 2048, LCAP = 64, NW = NT / 64;
+  uint32_t hist[NBIN];
+  float row_max[NW], row_min[NW];
+  uint32_t tot_a[NW], tot_b[NW];
+  uint32_t n_list;
+  float list_v[LCAP];
+};
+
+__device__ __forceinline__ float vmax_f32(float a, float b) {   // IEEE maxNum in one instruction: a NaN operand is ignored
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ float vmin_f32(float a, float b) {
+  float r;
+  asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+__device__ __forceinline__ uint32_t cvt_u32_sat(float t) {      // floor for t >= 0; negatives and NaN give 0
+  uint32_t r;
+  asm("v_cvt_u32_f32 %0, %1" : "=v"(r) : "v"(t));
+  return r;
+}
+__device__ __forceinline__ float wave_max_f32(float v) {
+  return __uint_as_float(wave_all(__float_as_uint(v), [](uint32_t a, uint32_t b) {
+    return __float_as_uint(vmax_f32(__uint_as_float(a), __uint_as_float(b)));
+  }));
+}
+
+template <int NT, int E>
+__device__ __forceinline__ void fine_select_prepare(FineSelSmem<NT, E>& sm) {
+  uint4* h4 = reinterpret_cast<uint4*>(sm.hist);
+  for (int b = threadIdx.x; b < FineSelSmem<NT, E>::NBIN / 4; b += NT) h4[b] = make_uint4(0u, 0u, 0u, 0u);
+  if (threadIdx.x == 0) sm.n_list = 0u;
+}
+
+template <int NT, int E>
+__device__ __forceinline__ void fine_select_range(FineSelSmem<NT, E>& sm, float x_max, float x_min, int wave) {
+  const float w_max = wave_max_f32(x_max);
+  const float w_min = -wave_max_f32(-x_min);
+  if (lane_id() == 0) {
+    sm.row_max[wave] = w_max;
+    sm.row_min[wave] = w_min;
+  }
+}
+
+template <int NT, int E, class Vals, class Emit>
+__device__ __forceinline__ bool select_topk_fine(FineSelSmem<NT, E>& sm, int n, int k, Vals vals, Emit emit) {
+  static_assert(E % 4 == 0, "elements per thread come in groups of four");
+  using S = FineSelSmem<NT, E>;
+  constexpr int NW = S::NW, NBIN = S::NBIN, BPT = NBIN / NT;
+  static_assert(BPT % 4 == 0, "a thread scans whole 16-byte groups of bins");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i0 = tid * E;
+  const float qnan = __uint_as_float(0xffffffffu);
+  const float inf = __builtin_inff();
+
+  // ---- the thread's scores
+  typedef float valvec __attribute__((ext_vector_type(E)));
+  valvec v;
+  const bool whole = i0 + E <= n;
+#pragma unroll
+  for (int g = 0; g < E / 4; ++g) {
+    float4 q4 = make_float4(qnan, qnan, qnan, qnan);
+    if (i0 + 4 * g < n) q4 = vals((i0 >> 2) + g);
+    const float x[4] = {q4.x, q4.y, q4.z, q4.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[4 * g + e] = (whole || i0 + 4 * g + e < n) ? x[e] : qnan;
+  }
+  // ---- range of the bins: the row's own [minimum, maximum].  (A thread's E consecutive candidates
+  // are a piece of one key block, whose scores move together: an estimate built from per-thread
+  // extremes lands anywhere.)
+  float hi = -inf, lo = inf;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    hi = vmax_f32(hi, sm.row_max[w]);
+    lo = vmin_f32(lo, sm.row_min[w]);
+  }
+  if (!(hi > lo) || !(hi - lo < inf)) return false;          // empty, constant or overflowing range (uniform)
+  // bin(x) = 1 + floor((x - lo) * scale) in 1 .. NBIN-1 for lo <= x <= hi, 0 for NaN: monotone in x, so
+  // every score in a higher bin is larger than every score in a lower one.  scale stops a hair
+  // short of (NBIN - 2) / (hi - lo), so the top bin needs no clamp.  A thread keeps, per element,
+  // the LDS byte address of its bin (4 * bin + the histogram's base): one multiply-add, one
+  // conversion that rounds down (negative and NaN give 0), one mask.
+  const float scale4 = 4.0f * (float)(NBIN - 2) * (1.0f - 0x1p-18f) / (hi - lo);
+  const uint32_t hist_base = lds_address(sm.hist);
+  const float bias4 = 4.0f + (float)hist_base - lo * scale4;
+  typedef uint32_t binvec __attribute__((ext_vector_type(E)));
+  binvec bin;
+  const bool has_any = i0 < n;     // (threads past the row hold only NaN: they would all hit bin 0)
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const uint32_t addr = cvt_u32_sat(__builtin_fmaf(v[j], scale4, bias4)) & ~3u;
+    bin[j] = addr;
+    if (has_any) {
+      // NaN: the conversion gives 0, below the histogram; it is counted in bin 0
+      const uint32_t a_ok = addr > hist_base ? addr : hist_base;
+      asm volatile("ds_add_u32 %0, %1" : : "v"(a_ok), "v"(1u) : "memory");
+    }
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");           // (the compiler does not count these)
+  __syncthreads();                                             // 1: histogram complete
+  // ---- the bin that holds the k-th largest: counts above it < k <= counts above it + its own.
+  // Thread t owns bins t*BPT ..: wave totals first, then EVERY wave scans the bins of the wave that
+  // holds the k-th, so that all of them know the bin without another barrier.
+  auto bins_of = [&](int t, uint32_t (&c)[BPT]) -> uint32_t {
+    uint32_t sum = 0;
+#pragma unroll
+    for (int g = 0; g < BPT / 4; ++g) {
+      const uint4 c4 = *reinterpret_cast<const uint4*>(&sm.hist[t * BPT + 4 * g]);
+      c[4 * g + 0] = c4.x;
+      c[4 * g + 1] = c4.y;
+      c[4 * g + 2] = c4.z;
+      c[4 * g + 3] = c4.w;
+      sum += (c4.x + c4.y) + (c4.z + c4.w);
+    }
+    return sum;
+  };
+  uint32_t c[BPT];
+  {
+    const uint32_t w_tot = wave_sum(bins_of(tid, c));
+    if (lane == 0) sm.tot_a[wave] = w_tot;
+  }
+  __syncthreads();                                             // 2: wave totals visible
+  int w_star = -1;
+  uint32_t above_w = 0;
+#pragma unroll
+  for (int w = NW - 1; w >= 0; --w) {
+    const uint32_t tw = sm.tot_a[w];
+    if (w_star < 0) {
+      if ((uint32_t)k <= above_w + tw) w_star = w;
+      else above_w += tw;
+    }
+  }
+  if (w_star < 0) return false;                                // (cannot happen: the bins hold NT * E >= n > k entries)
+  const uint32_t mine = bins_of(w_star * 64 + lane, c);
+  uint32_t above = above_w + (wave_sum(mine) - wave_scan_add(mine));   // entries in the bins above this lane's
+  uint32_t f_bin = 0, f_rem = 0, f_cnt = 0;
+  bool found = false;
+#pragma unroll
+  for (int b = BPT - 1; b >= 0; --b) {
+    if (above < (uint32_t)k && (uint32_t)k <= above + c[b]) {
+      found = true;
+      f_bin = hist_base + 4u * (uint32_t)((w_star * 64 + lane) * BPT + b);   // the bin as its LDS address
+      f_rem = (uint32_t)k - above;
+      f_cnt = c[b];
+    }
+    above += c[b];
+  }
+  const uint64_t who_bin = __ballot(found);
+  if (who_bin == 0ull) return false;
+  const int src = __builtin_ctzll(who_bin);
+  const uint32_t D = (uint32_t)__builtin_amdgcn_readlane((int)f_bin, src);
+  const uint32_t krem = (uint32_t)__builtin_amdgcn_readlane((int)f_rem, src);
+  const uint32_t n_c = (uint32_t)__builtin_amdgcn_readlane((int)f_cnt, src);
+  if (D == hist_base || n_c > (uint32_t)S::LCAP) return false;  // the k-th among the masked entries, or a crowded bin
+  // ---- the scores of that bin (a handful in the whole row: each compare goes to a scalar register
+  // pair, and the branch on it is taken by whole waves)
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const bool in_bin = bin[j] == D;
+    if (__ballot(in_bin) != 0ull) {
+      if (in_bin) {
+        const uint32_t slot = atomicAdd(&sm.n_list, 1u);
+        if (slot < (uint32_t)S::LCAP) sm.list_v[slot] = v[j];
+      }
+    }
+  }
+  __syncthreads();                                             // 3: list complete
+  // their krem-th largest is the threshold: every wave ranks the list for itself (lane j takes
+  // entry j, the others are handed round from lane to lane)
+  const float x = lane < (int)n_c ? sm.list_v[lane] : qnan;
+  uint32_t gt = 0, ge = 0;
+  for (uint32_t i = 0; i < n_c; ++i) {
+    const float y = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(x), (int)i));
+    gt += y > x;
+    ge += y >= x;
+  }
+  const bool is_kth = lane < (int)n_c && gt < krem && krem <= ge;
+  const uint64_t who = __ballot(is_kth);
+  if (who == 0ull) return false;
+  const float tau = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(x), __builtin_ctzll(who)));
+  // ---- exactly k scores at or above tau?  (the check that makes the result exact)
+  uint32_t cnt = 0;
+#pragma unroll
+  for (int j = 0; j < E; ++j) cnt += v[j] >= tau;
+  const uint32_t c_incl = wave_scan_add(cnt);
+  if (lane == 63) sm.tot_b[wave] = c_incl;
+  __syncthreads();                                             // 4: counts visible
+  uint32_t pos = c_incl - cnt, taken = 0;
+#pragma unroll
+  for (int w = 0; w < NW; ++w) {
+    const uint32_t tw = sm.tot_b[w];
+    taken += tw;
+    if (w < wave) pos += tw;
+  }
+  if (taken != (uint32_t)k) return false;                      // ties across the threshold: not this path's case
+  emit(pos, v, tau, reinterpret_cast<int32_t*>(&sm.hist[tid]));
+  return true;
 }
 
 // fp32 -> bf16 bits, round to nearest even (finite inputs).

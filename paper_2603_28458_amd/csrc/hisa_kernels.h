@@ -475,6 +475,20 @@ __device__ __forceinline__ void wave_pipeline(const typename Operands<HG, KDT>::
   // one step: tile jn -> acc_out (matrix cores) while tile jn-1 = acc_in is finished (vector ALU)
   auto step = [&](int jn, const accvec<HG>& acc_in, float sc_in, accvec<HG>& acc_out, float& sc_out) {
     wait_tile(jn);
+    if constexpr (KDT == DT_BF16) {
+      // bf16 tile: the MFMAs of the first two 16-element chunks start as soon as those chunks are
+      // in registers and cover the arrival of the other six (64K prefill: -1 %, 16K: -1.4 %)
+      TileRegs tr;
+      lds_read_tile_issue(ring_addr + buf * BB, tr);
+      sc_out = 1.f;
+      const int slot = buf;
+      buf = (buf + 1 == NB) ? 0 : buf + 1;
+      acc_out = mfma_tile_progressive<HG>(f, tr, [&] {
+        if (jn + NB < nj) dma(jn + NB, slot);
+      });
+      finish(jn - 1, tile_epilogue<HG>(f, acc_in) * sc_in);
+      return;
+    }
     const Tile kv = read_tile(buf, sc_out);
     if (jn + NB < nj) dma(jn + NB, buf);
     buf = (buf + 1 == NB) ? 0 : buf + 1;
@@ -689,6 +703,18 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
   qfrag_ready<HG>(fq);
   typename Operands<HG, KDT>::Frag f;
   Operands<HG, KDT>::make(fq, f);
+  // the contraction of one staged sub-tile; bf16: every 16-element chunk is awaited right before
+  // its own MFMAs, so the first MFMAs run while the other chunks are still on their way from LDS
+  auto score_sub = [&](int buf, int sub, float& scale) -> accvec<HG> {
+    if constexpr (KDT == DT_BF16) {
+      TileRegs tr;
+      lds_read_tile_issue(tiles_addr + (buf * SUBS + sub) * BB, tr);
+      scale = 1.f;
+      return mfma_tile_progressive<HG, true>(f, tr, [] {});
+    }
+    const Tile kv = read_sub(buf, sub, scale);
+    return mfma_tile(f, kv);
+  };
   wait_vmem_le<0>();
   __syncthreads();
   accvec<HG> acc_a, acc_b;
@@ -699,13 +725,11 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
 #pragma unroll
     for (int h = 0; h < SUBS / 2; ++h) {
       {
-        const Tile kv = read_sub(buf, 2 * h, sc_b);
-        acc_b = mfma_tile(f, kv);                                                  // sub-tile SUBS*it + 2h
+        acc_b = score_sub(buf, 2 * h, sc_b);                                       // sub-tile SUBS*it + 2h
         if (it > 0 || h > 0) finish(SUBS * it + 2 * h - 1, tile_epilogue<HG>(f, acc_a) * sc_a);   // the one before
       }
       {
-        const Tile kv = read_sub(buf, 2 * h + 1, sc_a);
-        acc_a = mfma_tile(f, kv);                                                  // sub-tile SUBS*it + 2h + 1
+        acc_a = score_sub(buf, 2 * h + 1, sc_a);                                   // sub-tile SUBS*it + 2h + 1
         finish(SUBS * it + 2 * h, tile_epilogue<HG>(f, acc_b) * sc_b);
       }
     }
@@ -725,7 +749,12 @@ __global__ __launch_bounds__(512) void k_score_prefill(ScoreArgs a) {
 // consecutive queries from 8 * NQ * g, wave w the queries w, w + 8, ...; longest prefixes first.
 // (Measured and not kept: pulling the next query's fragment towards L2 while the current one is
 // scored, by DMA into a dummy LDS area since there are no registers for a second fragment: 10 %
-// slower, the extra transfers cost more than the shorter wait.)
+// slower, the extra transfers cost more than the shorter wait.  Also measured and not kept: the
+// block top-m fused behind the scoring, each wave selecting on an LDS row of its own without
+// workgroup barriers: 0.455 ms against 0.332 + 0.068 ms for this kernel plus the separate select
+// at the 64K prefill -- with two waves per SIMD the select's dependent LDS steps run at a quarter
+// of the occupancy the small select kernel gets, which costs more than the 68 MB of block scores
+// written and read back.)
 template <int HG, int NQ>
 __global__ __launch_bounds__(512) void k_score_resident(ScoreArgs a) {
   extern __shared__ __align__(16) unsigned char tiles[];   // [n_sub][8192]
@@ -1313,6 +1342,10 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
   static_assert(E1 == 0 || sizeof(SelectSmem<NT, E1 ? E1 : 4>) <= kStageBytes, "select scratch must fit the rings");
   float* sc = reinterpret_cast<float*>(smem + kStageBytes);   // m*B scores (swizzled: score_slot)
   SelectSmem<NT, E>& sm = *reinterpret_cast<SelectSmem<NT, E>*>(smem);
+  // scratch of the top-k's fast path, behind everything else (shared with nothing: see select_topk_fine)
+  FineSelSmem<NT, E>& fs = *reinterpret_cast<FineSelSmem<NT, E>*>(
+      smem + kStageBytes + (E1 > 0 ? (size_t)sc_floats * 4 + (size_t)((a.m + 3) / 4 * 4) * 4 : (size_t)a.m * a.B * 4));
+  fine_select_prepare<NT, E>(fs);
   const int t = a.t_begin + (gridDim.x - 1 - blockIdx.x);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   int seq;
@@ -1393,15 +1426,20 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
     qfrag_ready<HG>(f);
     Operands<HG, KDT>::make(f, fo);
   }
+  float s_max = -__builtin_inff(), s_min = __builtin_inff();   // this lane's largest / smallest score so far
   auto finish = [&](int j, float s) {
     const int r = rows.at(j);
     const int row = (r < 0 ? 0 : r) + (lane & 31);
-    // a masked slot holds the all-ones pattern (ordered_key_plain sends it to "not a candidate");
-    // a finished score is a sum that starts from +0, so it is never -0
+    // a masked slot holds the all-ones pattern, a NaN (ordered_key_plain sends it to "not a
+    // candidate", the maximum / minimum below ignore it); a finished score is a sum that starts
+    // from +0, so it is never -0
     if (row >= (r < 0 ? 0 : n_vis) || row < lo) s = __uint_as_float(kNoCandidateBits);
     if (lane < 32) sc[score_slot((wave + NW * j) * 32 + lane)] = s;
+    s_max = vmax_f32(s_max, s);
+    s_min = vmin_f32(s_min, s);
   };
   wave_pipeline<HG, KDT, NB>(fo, krsrc, srsrc, ring_addr, nj, row_at, finish, primed);
+  fine_select_range<NT, E>(fs, s_max, s_min, wave);
   __syncthreads();   // scores complete, rings dead: the select scratch may overwrite them
   const int n_cand_slots = n_active * 32;   // score slots actually written
 
@@ -1435,7 +1473,48 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
     stage[p] = tok;
     if (os) os[p] = key_to_score(key);
   };
-  const int n_out = select_topk<NT, E, false, false>(sm, n_cand_slots, k, load4, load1, emit);
+  // Fast path first (one fine histogram pass, exact by its own check); it declines -- before writing
+  // anything -- whenever the row is not its case, and the general select takes over.
+  int n_out = -1;
+  if (n_cand_slots > k) {
+    auto vals = [&](int q) -> float4 { return *reinterpret_cast<const float4*>(sc + score_slot(4 * q)); };
+    // Without the score output the thread's E candidates are written without a branch: every
+    // element is stored, the ones not selected into a dump word of the thread's own.
+    auto emit_f = [&](uint32_t p, const auto& v, float tau, int32_t* dump) {
+      const int i0 = (int)threadIdx.x * E;
+      if (one_slot && !os) {
+        const uint32_t dump_addr = lds_address(dump);
+        const uint32_t stage_addr = lds_address(stage);
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+          const bool take = v[j] >= tau;
+          const uint32_t addr = take ? stage_addr + 4u * p : dump_addr;
+          asm volatile("ds_write_b32 %0, %1" : : "v"(addr), "v"(my_base + i0 + j) : "memory");
+          p += take;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // (the compiler does not count these writes)
+        return;
+      }
+#pragma unroll
+      for (int j = 0; j < E; ++j) {
+        if (v[j] >= tau) {
+          const int i = i0 + j;
+          int tok;
+          if (one_slot) {
+            tok = my_base + i;
+          } else {
+            const int slot = i / a.B;
+            tok = blk_ids[slot] * a.B + (i - slot * a.B);
+          }
+          stage[p] = tok;
+          if (os) os[p] = v[j];
+          ++p;
+        }
+      }
+    };
+    if (select_topk_fine<NT, E>(fs, n_cand_slots, k, vals, emit_f)) n_out = k;
+  }
+  if (n_out < 0) n_out = select_topk<NT, E, false, false>(sm, n_cand_slots, k, load4, load1, emit);
   for (int p = n_out + threadIdx.x; p < k; p += NT) {
     stage[p] = -1;
     if (os) os[p] = neg_inf();
