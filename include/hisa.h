@@ -187,6 +187,11 @@ int dsa_flat_indexer_topk(const hisa_queries* queries, const hisa_keys* keys, in
  * Algorithm 1 whole in one launch: Stage 1 (Eqs. 5-6) and Stage 2 (Eqs. 7-9) of each query run
  * back to back in one workgroup, the query is read once, the block scores and the kept block ids
  * never leave the CU.  Same results as hisa_block_score_topk followed by hisa_token_refine_topk.
+ * A convenience for callers that want one call and no workspace, NOT the fast path: on MI355X the
+ * two calls are quicker at every shape measured (prefill: the separate Stage 1 kernel shares each
+ * pooled-key tile between 8 queries or keeps the tiles resident; decode: the two calls spread a
+ * query's tiles over many compute units, one workgroup per query cannot), by 1 % (decode batch) to
+ * 18 % (1M-context chunk).
  *   pooled     [n_seq, s_max / B, d] BF16 (device, in), as hisa_pool_blocks writes it
  *   block_idx  [T, m] int32 (device, out) or NULL: the kept block ids, ascending then -1
  *   topk_idx / topk_scores: as hisa_token_refine_topk

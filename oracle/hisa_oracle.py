@@ -17,10 +17,10 @@ Everything is written out from the paper's definitions, in IEEE double:
 A library matmul (numpy, float64) serves as the contraction step; selection is a full sort.
 
 Readings taken where the paper is silent (each is listed in the design notes of the repository):
-  * positions are 0-based; query at position p sees keys s <= p (the "t <= k selects all prefix
-    tokens" regime of Section 4.1 makes the query's own key visible);
-  * the forced first block and the block containing the query count inside the budget m
-    ("candidate capacity mB", Section 4.1), so |C_t| = min(m, #visible blocks);
+  * positions are 0-based; query at position p sees keys s <= p (Section 4.1, boundary behaviour:
+    in the short-prefix regime the whole prefix is selected, which includes the query's own key);
+  * the forced first block and the block containing the query count inside the budget m (Section
+    4.1, boundary behaviour, counts m*B candidates at most), so |C_t| = min(m, #visible blocks);
   * a partial block is averaged over the tokens it holds; the pooled cache is a stored tensor, so
     the mean is rounded once (nearest-even) to the pooled dtype and Stage 1 reads the rounded value;
   * TopK orders by score descending, ties by lower index; with fewer candidates than the budget

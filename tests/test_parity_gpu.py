@@ -153,6 +153,28 @@ def test_ties_and_zero_scores():
     _run(wl, queries=sample_queries(wl, 100))
 
 
+@pytest.mark.parametrize("k_dtype", ["bf16", "fp8_e4m3"])
+def test_score_outliers_send_the_fused_topk_to_its_general_select(k_dtype):
+    # The fused Stage 2 first tries a one-pass top-k whose bins span the row's own score range; one key
+    # with 3000 times the usual norm inside the always-kept first block stretches that range until
+    # nearly every candidate shares a bin, and the kernel must fall back to its general select.  A
+    # second key of the same size with negative gates stretches the other end.
+    wl = W.make_workload(f"outlier_{k_dtype}", seq_len=3000, T=3000, H=64, d=128, B=128, m=8, k=512, q_dtype="bf16",
+                         k_dtype=k_dtype, seed=114)
+    if k_dtype == "bf16":
+        kf = W._bf16_bits_to_f32(wl.keys[0, 5]) * np.float32(3000.0)
+        wl.keys[0, 5] = W._to_bf16_bits(kf)
+    else:
+        wl.k_scale[0, 5] *= np.float32(3000.0)           # the fp8 codes stay, the per-token scale grows
+    _run(wl, queries=sample_queries(wl, 150))
+    if k_dtype == "bf16":
+        # gates of both signs: scores of both signs, the outlier's included.  (bf16 keys only: with signed
+        # gates a score is a difference of large terms, and the fp8 path's error, which scales with the
+        # terms, is then no longer small against the row maximum the regression bound is stated in.)
+        wl.w = (wl.w - np.float32(0.5)).astype(np.float32)
+        _run(wl, queries=sample_queries(wl, 150, seed=1))
+
+
 def test_negative_gates():
     wl = W.make_workload("negw", seq_len=1300, T=1300, H=64, d=128, B=128, m=5, k=256, q_dtype="bf16",
                          k_dtype="bf16", seed=113)
