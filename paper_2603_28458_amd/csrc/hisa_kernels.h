@@ -1427,14 +1427,24 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(Score
     Operands<HG, KDT>::make(f, fo);
   }
   float s_max = -__builtin_inff(), s_min = __builtin_inff();   // this lane's largest / smallest score so far
+  // score_slot of candidate tile * 32 + lane is tile * 32 + a lane pattern that depends on tile % 8
+  // only, and this wave's tiles (wave + NW * j) alternate between two values of it
+  static_assert((2 * NW) % 8 == 0, "a wave's tiles take two values modulo 8");
+  const int l31 = lane & 31;
+  const uint32_t pat0 = (uint32_t)(((((l31 >> 2) ^ wave) & 7) << 2) | (l31 & 3)) * 4u;
+  const uint32_t pat1 = (uint32_t)(((((l31 >> 2) ^ (wave + NW)) & 7) << 2) | (l31 & 3)) * 4u;
+  const uint32_t sc_addr = lds_address(sc);
+  const int lane_lo = l31 - lo;
   auto finish = [&](int j, float s) {
     const int r = rows.at(j);
-    const int row = (r < 0 ? 0 : r) + (lane & 31);
     // a masked slot holds the all-ones pattern, a NaN (ordered_key_plain sends it to "not a
     // candidate", the maximum / minimum below ignore it); a finished score is a sum that starts
-    // from +0, so it is never -0
-    if (row >= (r < 0 ? 0 : n_vis) || row < lo) s = __uint_as_float(kNoCandidateBits);
-    if (lane < 32) sc[score_slot((wave + NW * j) * 32 + lane)] = s;
+    // from +0, so it is never -0.  Visible: lo <= row < n_vis, i.e. unsigned(row - lo) < n_vis - lo
+    // (nothing, for a tile without a kept block).
+    const int span = r < 0 ? 0 : (n_vis - lo > 0 ? n_vis - lo : 0);
+    if ((uint32_t)((r < 0 ? 0 : r) + lane_lo) >= (uint32_t)span) s = __uint_as_float(kNoCandidateBits);
+    const uint32_t addr = sc_addr + (uint32_t)(wave + NW * j) * 128u + ((j & 1) ? pat1 : pat0);
+    if (lane < 32) asm volatile("ds_write_b32 %0, %1" : : "v"(addr), "v"(s) : "memory");
     s_max = vmax_f32(s_max, s);
     s_min = vmin_f32(s_min, s);
   };
