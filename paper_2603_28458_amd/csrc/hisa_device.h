@@ -1045,7 +1045,7 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
 
 // ------------------------------------------------------------------------------------------
 // Fast path of the top-k behind the fused Stage 2 scoring: ONE histogram pass with bins fine enough
-// (2048 over the row's own score range) that the bin holding the k-th score has a handful of
+// (2048 or more over the row's own score range) that the bin holding the k-th score has a handful of
 // entries, whose k-th is then found by counting.  The threshold tau is a score of the row, and the
 // path emits only after it has CHECKED that exactly k scores are >= tau: then those k are the top
 // k whatever the binning did (ties at tau are either all in or the check fails).  On any doubt -- a
@@ -1066,7 +1066,7 @@ __device__ __forceinline__ int select_topk(SelectSmem<THREADS, E>& sm, int n, in
 //                            word of the thread's own that may be overwritten.
 template <int NT, int E>
 struct FineSelSmem {
-  static constexpr int NBIN = 2048, LCAP = 64, NW = NT / 64;
+  static constexpr int NBIN = NT <= 512 ? 2048 : 4 * NT, LCAP = 64, NW = NT / 64;   // >= 4 bins per thread
   uint32_t hist[NBIN];
   float row_max[NW], row_min[NW];
   uint32_t tot_a[NW], tot_b[NW];

@@ -910,7 +910,66 @@ __global__ __launch_bounds__(THREADS) void k_select(SelectArgs a) {
     oi[p] = id;
     if (os) os[p] = key_to_score(key);
   };
-  const int n_out = select_topk<THREADS, E, true, MAP == MAP_BLOCKS>(sm, n, a.k, load4, load1, emit);
+  int n_out = -1;
+  if constexpr ((MAP == MAP_CAND || MAP == MAP_BLOCKS) && THREADS >= 256) {
+    // Candidate rows (Stage 2 behind the separate scoring kernel) and block-score rows (Stage 1)
+    // first try the one-pass top-k of the fused kernel: a handful of barriers instead of about
+    // sixteen, which is most of this kernel's time when a decode batch gives it a few rows.  It
+    // declines before writing anything if the row is not its case.  (Not for the one-wave rows of up
+    // to 512 entries: zeroing and scanning 2048 bins with 64 threads doubled Stage 1 of the
+    // prefills, 0.40 -> 0.76 ms at 64K.)  Stage 1's two forced blocks
+    // are the first and the last entry of the row: they are left out of the search, which then
+    // looks for k - 2 among the others, and take the first and the last output position.
+    __shared__ FineSelSmem<THREADS, E> fs;
+    constexpr int kForced = MAP == MAP_BLOCKS ? 2 : 0;
+    const int k_free = a.k - kForced;
+    if (k_free >= 1 && n - kForced > k_free) {
+      fine_select_prepare<THREADS, E>(fs);
+      const float qnan = __uint_as_float(0xffffffffu);
+      const int i0 = (int)threadIdx.x * E;
+      float4 mine[E / 4];
+      float x_max = -__builtin_inff(), x_min = __builtin_inff();
+#pragma unroll
+      for (int g = 0; g < E / 4; ++g) {
+        const u32x4v r = __builtin_amdgcn_raw_buffer_load_b128(rrow, (i0 + 4 * g) * 4, 0, 0);   // zeros past the row
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = i0 + 4 * g + e;
+          const float xe = __uint_as_float(r[e]);
+          bool cand = i < n && xe != neg_inf();          // masked slots hold -inf in global memory
+          if (kForced) cand = cand && i != first_vis && i != n_last;
+          x[e] = cand ? xe : qnan;
+          x_max = vmax_f32(x_max, x[e]);
+          x_min = vmin_f32(x_min, x[e]);
+        }
+        mine[g] = make_float4(x[0], x[1], x[2], x[3]);
+      }
+      fine_select_range<THREADS, E>(fs, x_max, x_min, (int)threadIdx.x >> 6);
+      __syncthreads();
+      auto vals = [&](int q) -> float4 { return mine[q - (i0 >> 2)]; };
+      auto emit_f = [&](uint32_t p, const auto& v, float tau, int32_t*) {
+        p += kForced ? 1 : 0;
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+          if (v[j] >= tau) {
+            emit((int)p, i0 + j, ordered_key(v[j]));
+            ++p;
+          }
+        }
+      };
+      if (select_topk_fine<THREADS, E>(fs, n, k_free, vals, emit_f)) {
+        n_out = a.k;
+        if (kForced && threadIdx.x == 0) {
+          emit(0, first_vis, 0xffffffffu);
+          emit(a.k - 1, n_last, 0xffffffffu);
+        }
+      } else {
+        __syncthreads();
+      }
+    }
+  }
+  if (n_out < 0) n_out = select_topk<THREADS, E, true, MAP == MAP_BLOCKS>(sm, n, a.k, load4, load1, emit);
   for (int p = n_out + threadIdx.x; p < a.k; p += THREADS) {
     oi[p] = -1;
     if (os) os[p] = neg_inf();
