@@ -243,11 +243,15 @@ int hisa_index_iou(const int32_t* a_idx, const int32_t* b_idx, int32_t T, int32_
  * iters * 16 v_mfma_f32_32x32x16_bf16 and nothing else; *flop (host) receives the flop count of the
  * launch, out (device, 512 * 256 floats) receives values that only keep the loop alive.
  * hisa_probe_mfma_fp8: the same with iters * 8 v_mfma_f32_32x32x64_f8f6f4 (e4m3 x e4m3), the
- * instruction the fp8-key scoring runs on.
+ * instruction the fp8-key scoring runs on.  hisa_probe_mfma_toggling: either loop (fp8 = 0 / 1) on
+ * operands that differ per lane and per instruction (pseudo-random signs and mantissas): the rate
+ * the matrix cores sustain once their inputs toggle as real data does, which on this chip is below
+ * the rate of the two constant-operand probes because the clock drops under that load.
  */
 int hisa_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 int hisa_probe_mfma(float* out, int32_t iters, double* flop, void* stream);
 int hisa_probe_mfma_fp8(float* out, int32_t iters, double* flop, void* stream);
+int hisa_probe_mfma_toggling(float* out, int32_t iters, int32_t fp8, double* flop, void* stream);
 
 /* Recommended workspace size in bytes for `op` (HISA_OP_*) at these shapes; 0 if none is needed
  * or the shapes are invalid.  `want_scores` != 0: the optional full score output of Stage 1 / 2

@@ -435,6 +435,20 @@ int hisa_probe_mfma_fp8(float* out, int32_t iters, double* flop, void* stream) {
   return launch_status();
 }
 
+int hisa_probe_mfma_toggling(float* out, int32_t iters, int32_t fp8, double* flop, void* stream) {
+  if (!out || !flop) return HISA_ERR_NULL;
+  if (iters < 1 || (fp8 != 0 && fp8 != 1)) return HISA_ERR_SHAPE;
+  const int wgs = 512;
+  if (fp8) {
+    hipLaunchKernelGGL(k_probe_mfma_toggling<true>, dim3(wgs), dim3(256), 0, (hipStream_t)stream, out, iters);
+    *flop = (double)wgs * 4.0 * iters * 8.0 * (2.0 * 32 * 32 * 64);
+  } else {
+    hipLaunchKernelGGL(k_probe_mfma_toggling<false>, dim3(wgs), dim3(256), 0, (hipStream_t)stream, out, iters);
+    *flop = (double)wgs * 4.0 * iters * 16.0 * (2.0 * 32 * 32 * 16);
+  }
+  return launch_status();
+}
+
 int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, const void* pooled,
                           int32_t pooled_dtype, int32_t B, int32_t m, int32_t* block_idx,
                           float* block_scores, void* ws, size_t ws_bytes, void* stream) {

@@ -307,6 +307,63 @@ __global__ __launch_bounds__(256) void k_probe_mfma_fp8(float* out, int iters) {
   out[(long)blockIdx.x * 256 + threadIdx.x] = (acc[0][0] + acc[1][5]) + (acc[2][9] + acc[3][15]);
 }
 
+// The same two loops on operands that differ from lane to lane and from one MFMA to the next
+// (pseudo-random signs and mantissas, exponents within a factor of 8 of one): what the matrix cores
+// sustain when their inputs toggle as real data does.  With the constant small integers of the two
+// probes above the chip holds its full clock; with these it does not.
+__device__ __forceinline__ uint32_t probe_hash(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x7feb352dU;
+  x ^= x >> 15;
+  x *= 0x846ca68bU;
+  x ^= x >> 16;
+  return x;
+}
+
+template <bool FP8>
+__global__ __launch_bounds__(256) void k_probe_mfma_toggling(float* out, int iters) {
+  // four A and four B operands per lane, 32 bytes each (the bf16 instruction reads the first 16)
+  i32x8 a[4], b[4];
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t h = probe_hash(threadIdx.x * 64u + n * 8u + e);
+      const uint32_t g = probe_hash(h + 77u + blockIdx.x);
+      if constexpr (FP8) {
+        // e4m3 bytes: sign, exponent field 4..7 (2^-3 .. 1), three mantissa bits; never the NaN code
+        a[n][e] = (int)((h & 0x87878787u) | 0x20202020u | ((h >> 1) & 0x18181818u));
+        b[n][e] = (int)((g & 0x87878787u) | 0x20202020u | ((g >> 1) & 0x18181818u));
+      } else {
+        // bf16 halves: sign, exponent field 124..127, seven mantissa bits
+        a[n][e] = (int)((h & 0x807f807fu) | 0x3e003e00u | ((h >> 2) & 0x01800180u));
+        b[n][e] = (int)((g & 0x807f807fu) | 0x3e003e00u | ((g >> 2) & 0x01800180u));
+      }
+    }
+  f32x16 acc[4];
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[n][i] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < (FP8 ? 2 : 4); ++r)
+#pragma unroll
+      for (int n = 0; n < 4; ++n) {
+        const i32x8 av = a[(n + r) & 3], bv = b[(n + 2 * r + 1) & 3];
+        if constexpr (FP8) {
+          acc[n] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(av, bv, acc[n], 0, 0, 0, 0, 0, 0);
+        } else {
+          const u32x4v a4 = {(uint32_t)av[0], (uint32_t)av[1], (uint32_t)av[2], (uint32_t)av[3]};
+          const u32x4v b4 = {(uint32_t)bv[0], (uint32_t)bv[1], (uint32_t)bv[2], (uint32_t)bv[3]};
+          acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a4),
+                                                           __builtin_bit_cast(bf16x8, b4), acc[n], 0, 0, 0);
+        }
+      }
+  }
+  out[(long)blockIdx.x * 256 + threadIdx.x] = (acc[0][0] + acc[1][5]) + (acc[2][9] + acc[3][15]);
+}
+
 __global__ __launch_bounds__(256) void k_fill_f32(float* p, long n, float v) {
   for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long)gridDim.x * 256) p[i] = v;
 }
@@ -396,6 +453,10 @@ __device__ __forceinline__ TileLoc tile_loc(const ScoreArgs& a, int t, int v, bo
 //   * copies the staged tile into registers as MFMA B operands (which frees the LDS tile),
 //   * runs the 16 MFMAs of tile j while the vector ALU does the ReLU / gate / head-sum epilogue of
 //     tile j-1 (two accumulator sets swap roles, the loop is unrolled by two).
+// (Measured and not kept: the operand reads of tile j+1 requested from LDS while the MFMAs of tile j
+// run, into a second register set paid for by one accumulator set per head block, so that no MFMA of
+// a wave waits on an LDS read: Stage 2 of the 64K prefill 3-4 % slower with bf16 and with fp8 keys,
+// wherever in the step the next DMA was issued.  The step is not waiting on LDS latency.)
 // row_at(j): first key row of tile j (wave-uniform, a row inside the sequence's key array);
 // finish(j, s): lane l < 32 receives the score of key row_at(j) + l (fp8: already scaled).
 template <int KDT>
@@ -1386,6 +1447,9 @@ __device__ __forceinline__ void stage1_in_workgroup(const QFrag<HG>& f, const Sc
 // score area, select_topk keeps m of them (first and own block forced, E1 blocks per thread),
 // and the kept ids stay in LDS for Stage 2 (and are written to block_idx_out if given).
 // sc_floats: size of the score area (>= m * B, and >= NW * 64 * E1 when E1 > 0).
+// (Measured and not kept: each workgroup, once its scoring is over, pulling the query of the
+// workgroup 512 or 1024 positions behind it into the XCD's L2: 64K prefill +2 %, 16K -1 %, fp8 keys
+// and the 1M chunk unchanged.  The first read of a query is not what a workgroup waits for.)
 template <int HG, int KDT, int NW, int NB, int E, int E1 = 0>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_refine_fused(ScoreArgs a, int k,
                                                                            int32_t* topk_idx,

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "lib", "libh
 
 EXPORTS = ["hisa_pool_blocks", "hisa_pool_append", "hisa_block_score_topk", "hisa_token_refine_topk",
            "hisa_block_sparse_tokens", "hisa_index_iou", "dsa_flat_indexer_topk", "hisa_workspace_bytes",
-           "hisa_status_string", "hisa_version", "hisa_probe_copy", "hisa_probe_mfma", "hisa_probe_mfma_fp8", "hisa_indexer_topk", "hisa_pool_blocks_max",
+           "hisa_status_string", "hisa_version", "hisa_probe_copy", "hisa_probe_mfma", "hisa_probe_mfma_fp8", "hisa_probe_mfma_toggling", "hisa_indexer_topk", "hisa_pool_blocks_max",
            "hisa_token_refine_topk_static"]
 STATIC_SCRATCH_BYTES = 16 << 20
 
@@ -88,6 +88,8 @@ def lib() -> C.CDLL:
         L.hisa_probe_mfma.restype = C.c_int
         L.hisa_probe_mfma_fp8.argtypes = [vp, i32, C.POINTER(C.c_double), vp]
         L.hisa_probe_mfma_fp8.restype = C.c_int
+        L.hisa_probe_mfma_toggling.argtypes = [vp, i32, i32, C.POINTER(C.c_double), vp]
+        L.hisa_probe_mfma_toggling.restype = C.c_int
         L.hisa_status_string.argtypes = [C.c_int]
         L.hisa_status_string.restype = C.c_char_p
         L.hisa_version.argtypes = []
@@ -355,6 +357,15 @@ def hisa_probe_mfma_fp8(out: torch.Tensor, iters: int, stream=None) -> float:
     assert out.dtype == torch.float32 and out.numel() >= 512 * 256
     flop = C.c_double(0.0)
     _check(lib().hisa_probe_mfma_fp8(_ptr(out), iters, C.byref(flop), _stream(stream)), "hisa_probe_mfma_fp8")
+    return flop.value
+
+
+def hisa_probe_mfma_toggling(out: torch.Tensor, iters: int, fp8: bool = False, stream=None) -> float:
+    """Either MFMA probe on operands that differ per lane and per instruction (pseudo-random values)."""
+    assert out.dtype == torch.float32 and out.numel() >= 512 * 256
+    flop = C.c_double(0.0)
+    _check(lib().hisa_probe_mfma_toggling(_ptr(out), iters, 1 if fp8 else 0, C.byref(flop), _stream(stream)),
+           "hisa_probe_mfma_toggling")
     return flop.value
 
 

@@ -154,6 +154,9 @@ def test_validation_of_the_single_launch_call_and_the_probes(lib):
     assert lib.hisa_probe_mfma(fake, 0, C.byref(flop), None) == 2
     assert lib.hisa_probe_mfma_fp8(None, 10, C.byref(flop), None) == 1
     assert lib.hisa_probe_mfma_fp8(fake, 0, C.byref(flop), None) == 2
+    assert lib.hisa_probe_mfma_toggling(None, 10, 0, C.byref(flop), None) == 1
+    assert lib.hisa_probe_mfma_toggling(fake, 0, 1, C.byref(flop), None) == 2
+    assert lib.hisa_probe_mfma_toggling(fake, 10, 2, C.byref(flop), None) == 2
 
 
 def test_workspace_sizes(lib):
