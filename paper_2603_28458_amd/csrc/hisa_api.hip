@@ -258,6 +258,30 @@ int launch_indexer(const ScoreArgs& a, const void* pooled, int k, int32_t* block
              : launch_indexer_hg<1, KDT, NW, 32>(a, pooled, k, block_idx_out, topk_idx, topk_scores, st);
 }
 
+// Stage 1 of a small batch in one launch (k_stage1_query): M blocks per sequence, E1 per thread.
+template <int HG, int E1>
+int launch_stage1_query_e(const ScoreArgs& a, const void* pooled, int M, int32_t* block_idx, hipStream_t st) {
+  const int sc_floats = (int)round_up(M, 32);
+  // up to 2048 blocks a ring of two tiles per wave fits beside the scores, above that a ring of one
+  constexpr int NB = E1 <= 4 ? 2 : 1;
+  const size_t sh = (size_t)8 * NB * 8192 + (size_t)sc_floats * 4 + (size_t)round_up(a.m, 4) * 4 + (size_t)HG * 8192;
+  constexpr auto kern = k_stage1_query<HG, E1, NB>;
+  if (raise_lds_limit<kern>(sh)) return HISA_ERR_LAUNCH;
+  hipLaunchKernelGGL(kern, dim3(a.t_count), dim3(512), sh, st, a, pooled, block_idx, sc_floats);
+  return HISA_OK;
+}
+
+constexpr int kStage1QueryMaxT = 256;    // one workgroup per query: while the queries are fewer than the CUs
+constexpr int kStage1QueryMaxM = 8192;   // 512 threads x 16 blocks
+
+int launch_stage1_query(const ScoreArgs& a, const void* pooled, int M, int32_t* block_idx, hipStream_t st) {
+  if (M <= 2048)
+    return a.H == 64 ? launch_stage1_query_e<2, 4>(a, pooled, M, block_idx, st)
+                     : launch_stage1_query_e<1, 4>(a, pooled, M, block_idx, st);
+  return a.H == 64 ? launch_stage1_query_e<2, 16>(a, pooled, M, block_idx, st)
+                   : launch_stage1_query_e<1, 16>(a, pooled, M, block_idx, st);
+}
+
 // Flat indexer: rows of queries scored per chunk, and the size of the segment-merge area.
 struct FlatPlan {
   long ld;          // score row stride (floats)
@@ -297,7 +321,7 @@ const char* hisa_status_string(int status) {
   }
 }
 
-const char* hisa_version(void) { return "0.2"; }
+const char* hisa_version(void) { return "0.3"; }
 
 
 static int pool_blocks_impl(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_t blk_end,
@@ -471,15 +495,26 @@ int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, co
   const int T = queries->T;
   hipStream_t s = (hipStream_t)stream;
   ScoreArgs a = base_args(queries, keys);
-  a.keys = pooled;
-  a.k_scale = nullptr;
-  a.rows_per_seq = M;
-  a.pos_div = B;
   float* J = block_scores;
   if (!J) {
     if (!ws || ws_bytes < (size_t)T * M * 4) return HISA_ERR_WORKSPACE;
     J = (float*)ws;
   }
+  if (path == PATH_MFMA && pooled_dtype == HISA_BF16 && !block_scores && T <= kStage1QueryMaxT &&
+      M <= kStage1QueryMaxM) {
+    // a decode batch: scoring and selection of a query in one workgroup, nothing through the workspace
+    a.B = B;
+    a.m = m;
+    a.t_begin = 0;
+    a.t_count = T;
+    st = launch_stage1_query(a, pooled, M, block_idx, s);
+    if (st) return st;
+    return launch_status();
+  }
+  a.keys = pooled;
+  a.k_scale = nullptr;
+  a.rows_per_seq = M;
+  a.pos_div = B;
   a.out = J;
   a.ld = M;
   a.t_begin = 0;

@@ -1395,10 +1395,12 @@ __global__ __launch_bounds__(StreamSelect::kThreads, 8) void k_select_stream(Sel
 // a.m of them with the first visible and the query's own block forced (E1 blocks per thread: NW * 64 * E1 >= n_blocks), and the kept ids go
 // to blk_lds[0 .. a.m) ascending, -1 padded.  smem: the NW * NB tile rings of TILE bytes (reused
 // by the select).  Ends with a barrier: ids visible, score area and rings free again.
+// primed: every wave has already issued the DMA of its first tile (blocks 32 * wave ..) into its
+// ring slot 0, and that DMA has completed.
 template <int HG, int NW, int NB, int E1, int TILE>
 __device__ __forceinline__ void stage1_in_workgroup(const QFrag<HG>& f, const ScoreArgs& a, const void* pooled,
                                                     int seq, int pos, int lo, int n_blocks, unsigned char* smem,
-                                                    float* sc, int32_t* blk_lds, int wave) {
+                                                    float* sc, int32_t* blk_lds, int wave, bool primed = false) {
   constexpr int NT = NW * 64;
   const int lane = threadIdx.x & 63;
   const int n_bvis = pos < 0 ? 0 : pos / a.B + 1;
@@ -1413,7 +1415,8 @@ __device__ __forceinline__ void stage1_in_workgroup(const QFrag<HG>& f, const Sc
       [&](int j, float s) {
         const int b = (wave + NW * j) * 32 + (lane & 31);
         if (lane < 32) sc[b] = (b < n_bvis && b >= b_first) ? s : neg_inf();
-      });
+      },
+      primed && nj1 > 0);
   __syncthreads();   // block scores complete, rings dead
   {
     SelectSmem<NT, E1>& sm1 = *reinterpret_cast<SelectSmem<NT, E1>*>(smem);
@@ -1433,6 +1436,46 @@ __device__ __forceinline__ void stage1_in_workgroup(const QFrag<HG>& f, const Sc
     for (int p = n_kept + threadIdx.x; p < a.m; p += NT) blk_lds[p] = -1;
   }
   __syncthreads();
+}
+
+// ------------------------------------------------------------------------------------------
+// Stage 1 (Eqs. 5-6) of a FEW queries (a decode batch), one launch: one workgroup of 8 waves per
+// query loads the query fragment, scores the pooled keys of the visible blocks into LDS and keeps m
+// of them there; only the m ids leave the CU.  Against the scoring launch plus the select launch
+// this saves a launch, the round trip of the block scores through HBM and the second query read;
+// with one workgroup per query it only pays while the queries are fewer than the CUs.
+// sc_floats >= the block count rounded up to 32; LDS: the tile rings, sc_floats scores, m ids
+// (rounded up to 4), HG * 8192 bytes for the query fragment.
+template <int HG, int E1, int NB>
+__global__ __launch_bounds__(512) void k_stage1_query(ScoreArgs a, const void* pooled, int32_t* block_idx_out,
+                                                      int sc_floats) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int NW = 8, NT = NW * 64, TILE = 8192;
+  constexpr size_t kStageBytes = (size_t)NW * NB * TILE;
+  static_assert(sizeof(SelectSmem<NT, E1>) <= kStageBytes, "select scratch must fit the rings");
+  float* sc = reinterpret_cast<float*>(smem + kStageBytes);
+  int32_t* blk_lds = reinterpret_cast<int32_t*>(sc + sc_floats);
+  unsigned char* q_lds = reinterpret_cast<unsigned char*>(blk_lds + (a.m + 3) / 4 * 4);   // HG * 8192 bytes
+  const int t = a.t_begin + blockIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  int seq;
+  const int pos = query_pos(a, t, seq);
+  const int lo = query_lo(a.q_lo, t, pos);
+  const int n_blocks = (int)(a.rows_per_seq / a.B);
+  // the query fragment is staged in an area of its own, so that every wave's first tile of pooled
+  // keys can be requested right behind it: one memory latency for both
+  QFrag<HG> f;
+  qfrag_shared_request<HG, NW>(f, (const uint16_t*)a.q + (long)t * a.H * kD, a.w + (long)t * a.H,
+                               (long)a.H * kD * 2, lds_address(q_lds), wave);
+  {
+    const __amdgpu_buffer_rsrc_t prsrc =
+        key_buffer((const char*)pooled + (long)seq * n_blocks * kD * 2, (long)n_blocks * kD * 2);
+    tile_dma<DT_BF16>(prsrc, prsrc, lds_address(smem) + wave * NB * TILE, wave * 32);
+  }
+  qfrag_shared_complete<HG>(f, lds_address(q_lds));
+  qfrag_ready<HG>(f);
+  stage1_in_workgroup<HG, NW, NB, E1, TILE>(f, a, pooled, seq, pos, lo, n_blocks, smem, sc, blk_lds, wave, true);
+  for (int p = threadIdx.x; p < a.m; p += NT) block_idx_out[(long)t * a.m + p] = blk_lds[p];
 }
 
 // ------------------------------------------------------------------------------------------

@@ -72,6 +72,16 @@ def test_decode_batch_ragged_lengths(k_dtype):
     _run(wl)
 
 
+@pytest.mark.parametrize("H", [64, 32])
+def test_decode_batch_with_thousands_of_blocks(H):
+    # Stage 1 of a small batch runs in one launch (scores and kept ids stay in LDS): here with 3750
+    # blocks per sequence (B = 32), beyond the 2048 that the deeper tile ring covers, ragged lengths,
+    # one sequence shorter than a block
+    wl = W.make_workload(f"decode_blocks_{H}", n_seq=4, seq_len=[120000, 65537, 40, 99999], T=4, H=H, d=128, B=32,
+                         m=40, k=1024, q_dtype="bf16", k_dtype="bf16", mode="decode", n_needles=2, seed=141)
+    _run(wl)
+
+
 @pytest.mark.parametrize("k_dtype", ["bf16", "fp8_e4m3"])
 def test_packed_varlen_prefill(k_dtype):
     # three sequences of different lengths prefilled in one call (each starts at a block boundary
