@@ -1123,17 +1123,32 @@ __device__ __forceinline__ bool select_topk_fine(FineSelSmem<NT, E>& sm, int n, 
   const float qnan = __uint_as_float(0xffffffffu);
   const float inf = __builtin_inff();
 
-  // ---- the thread's scores
+  // ---- the thread's scores.  A thread lies wholly inside the row, wholly outside it (only NaN), or
+  // -- one thread of the row at most -- across its end: only that one checks every element.
   typedef float valvec __attribute__((ext_vector_type(E)));
   valvec v;
   const bool whole = i0 + E <= n;
+  const bool has_any = i0 < n;
 #pragma unroll
-  for (int g = 0; g < E / 4; ++g) {
-    float4 q4 = make_float4(qnan, qnan, qnan, qnan);
-    if (i0 + 4 * g < n) q4 = vals((i0 >> 2) + g);
-    const float x[4] = {q4.x, q4.y, q4.z, q4.w};
+  for (int j = 0; j < E; ++j) v[j] = qnan;
+  if (whole) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) v[4 * g + e] = (whole || i0 + 4 * g + e < n) ? x[e] : qnan;
+    for (int g = 0; g < E / 4; ++g) {
+      const float4 q4 = vals((i0 >> 2) + g);
+      v[4 * g + 0] = q4.x;
+      v[4 * g + 1] = q4.y;
+      v[4 * g + 2] = q4.z;
+      v[4 * g + 3] = q4.w;
+    }
+  } else if (has_any) {
+#pragma unroll
+    for (int g = 0; g < E / 4; ++g) {
+      float4 q4 = make_float4(qnan, qnan, qnan, qnan);
+      if (i0 + 4 * g < n) q4 = vals((i0 >> 2) + g);
+      const float x[4] = {q4.x, q4.y, q4.z, q4.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[4 * g + e] = (i0 + 4 * g + e < n) ? x[e] : qnan;
+    }
   }
   // ---- range of the bins: the row's own [minimum, maximum].  (A thread's E consecutive candidates
   // are a piece of one key block, whose scores move together: an estimate built from per-thread
@@ -1155,18 +1170,21 @@ __device__ __forceinline__ bool select_topk_fine(FineSelSmem<NT, E>& sm, int n, 
   const float bias4 = 4.0f + (float)hist_base - lo * scale4;
   typedef uint32_t binvec __attribute__((ext_vector_type(E)));
   binvec bin;
-  const bool has_any = i0 < n;     // (threads past the row hold only NaN: they would all hit bin 0)
 #pragma unroll
-  for (int j = 0; j < E; ++j) {
-    const uint32_t addr = cvt_u32_sat(__builtin_fmaf(v[j], scale4, bias4)) & ~3u;
-    bin[j] = addr;
-    if (has_any) {
+  for (int j = 0; j < E; ++j) bin[j] = 0u;
+  if (has_any) {                   // (threads past the row hold only NaN: they would all hit bin 0)
+    uint32_t one;
+    asm volatile("v_mov_b32 %0, 1" : "=v"(one));               // (kept in a register across the atomics below)
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      const uint32_t addr = cvt_u32_sat(__builtin_fmaf(v[j], scale4, bias4)) & ~3u;
+      bin[j] = addr;
       // NaN: the conversion gives 0, below the histogram; it is counted in bin 0
       const uint32_t a_ok = addr > hist_base ? addr : hist_base;
-      asm volatile("ds_add_u32 %0, %1" : : "v"(a_ok), "v"(1u) : "memory");
+      asm volatile("ds_add_u32 %0, %1" : : "v"(a_ok), "v"(one) : "memory");
     }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");         // (the compiler does not count these)
   }
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");           // (the compiler does not count these)
   __syncthreads();                                             // 1: histogram complete
   // ---- the bin that holds the k-th largest: counts above it < k <= counts above it + its own.
   // Thread t owns bins t*BPT ..: wave totals first, then EVERY wave scans the bins of the wave that
@@ -1222,15 +1240,21 @@ __device__ __forceinline__ bool select_topk_fine(FineSelSmem<NT, E>& sm, int n, 
   const uint32_t krem = (uint32_t)__builtin_amdgcn_readlane((int)f_rem, src);
   const uint32_t n_c = (uint32_t)__builtin_amdgcn_readlane((int)f_cnt, src);
   if (D == hist_base || n_c > (uint32_t)S::LCAP) return false;  // the k-th among the masked entries, or a crowded bin
-  // ---- the scores of that bin (a handful in the whole row: each compare goes to a scalar register
-  // pair, and the branch on it is taken by whole waves)
+  // ---- the scores of that bin (a handful in the whole row): eight compares at a time are OR-ed in
+  // scalar registers, and only a wave that holds one of them walks those eight elements
+  constexpr int G = E >= 8 ? 8 : 4;
 #pragma unroll
-  for (int j = 0; j < E; ++j) {
-    const bool in_bin = bin[j] == D;
-    if (__ballot(in_bin) != 0ull) {
-      if (in_bin) {
-        const uint32_t slot = atomicAdd(&sm.n_list, 1u);
-        if (slot < (uint32_t)S::LCAP) sm.list_v[slot] = v[j];
+  for (int g = 0; g < E / G; ++g) {
+    bool any = false;
+#pragma unroll
+    for (int j = g * G; j < (g + 1) * G; ++j) any |= bin[j] == D;
+    if (__ballot(any) != 0ull) {
+#pragma unroll
+      for (int j = g * G; j < (g + 1) * G; ++j) {
+        if (bin[j] == D) {
+          const uint32_t slot = atomicAdd(&sm.n_list, 1u);
+          if (slot < (uint32_t)S::LCAP) sm.list_v[slot] = v[j];
+        }
       }
     }
   }
