@@ -404,7 +404,37 @@ __global__ __launch_bounds__(256) void k_score_ranges_f32(ScoreArgs a, int keys_
     if (valid) {
       const float4* kr = reinterpret_cast<const float4*>(kbase + row * d);
       s = 0.f;
-      for (int j = 0; j < H; ++j) {
+      // Four heads per pass over the key row (its loads are then independent of each other and four
+      // deep, instead of one dependent load per 4 multiply-adds); every head keeps its own four
+      // partial sums in the order of the one-head loop below, so the grouping changes no bit.
+      int j = 0;
+      for (; j + 4 <= H; j += 4) {
+        const float4* qr = reinterpret_cast<const float4*>(qs + j * d);
+        const int dq = d >> 2;
+        float p[4][4];
+#pragma unroll
+        for (int h = 0; h < 4; ++h)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) p[h][e] = 0.f;
+#pragma unroll 4
+        for (int i = 0; i < dq; ++i) {
+          const float4 kv = kr[i];
+#pragma unroll
+          for (int h = 0; h < 4; ++h) {
+            const float4 qv = qr[h * dq + i];
+            p[h][0] = __builtin_fmaf(qv.x, kv.x, p[h][0]);
+            p[h][1] = __builtin_fmaf(qv.y, kv.y, p[h][1]);
+            p[h][2] = __builtin_fmaf(qv.z, kv.z, p[h][2]);
+            p[h][3] = __builtin_fmaf(qv.w, kv.w, p[h][3]);
+          }
+        }
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+          const float dot = (p[h][0] + p[h][1]) + (p[h][2] + p[h][3]);
+          s = __builtin_fmaf(qs[H * d + j + h], __builtin_fmaxf(dot, 0.f), s);
+        }
+      }
+      for (; j < H; ++j) {
         const float4* qr = reinterpret_cast<const float4*>(qs + j * d);
         float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
         for (int i = 0; i < d / 4; ++i) {
