@@ -1520,6 +1520,9 @@ __global__ __launch_bounds__(512) void k_stage1_query(ScoreArgs a, const void* p
 // score area, select_topk keeps m of them (first and own block forced, E1 blocks per thread),
 // and the kept ids stay in LDS for Stage 2 (and are written to block_idx_out if given).
 // sc_floats: size of the score area (>= m * B, and >= NW * 64 * E1 when E1 > 0).
+// (Measured and not kept: the tiles of a query handed out to its waves at run time from an LDS
+// counter instead of dealt round robin, so that the waves finish together: 7-10 % slower with 4
+// waves per query, 2 % with 8, whose waves wait longest for each other.)
 // (Measured and not kept: each workgroup, once its scoring is over, pulling the query of the
 // workgroup 512 or 1024 positions behind it into the XCD's L2: 64K prefill +2 %, 16K -1 %, fp8 keys
 // and the 1M chunk unchanged.  The first read of a query is not what a workgroup waits for.)
