@@ -105,6 +105,15 @@ def test_packed_sequences_with_straddling_blocks(k_dtype):
     _run(wl, queries=qs)
 
 
+def test_packed_sequences_in_a_small_batch():
+    # at most 256 queries: Stage 1 runs in one launch per batch (scores and kept ids stay in LDS); here
+    # with four short sequences end to end in one key stream, blocks of 32 straddling their boundaries,
+    # every query of the stream
+    base = W.make_workload("pk_small", n_seq=4, seq_len=[70, 33, 101, 45], T=249, H=64, d=128, B=32, m=3, k=64,
+                           q_dtype="bf16", k_dtype="bf16", mode="varlen", seed=134)
+    _run(W.pack(base))
+
+
 def test_packed_sequences_fp32_and_long_rows():
     # the fp32 path, and a stream long enough for the streaming top-k of the flat indexer
     base = W.make_workload("pk_f32", n_seq=4, seq_len=[100, 45, 300, 77], T=522, H=4, d=64, B=16, m=4, k=32,
