@@ -321,7 +321,7 @@ const char* hisa_status_string(int status) {
   }
 }
 
-const char* hisa_version(void) { return "0.3"; }
+const char* hisa_version(void) { return "0.4"; }
 
 
 static int pool_blocks_impl(const hisa_keys* keys, int32_t B, int32_t blk_begin, int32_t blk_end,

@@ -709,7 +709,8 @@ __global__ __launch_bounds__(256, 2) void k_score_ranges(ScoreArgs a) {
 // the MFMAs of one sub-tile over the epilogue of the previous one (two accumulator sets).  Longest
 // prefixes launch first.  Used by the flat DSA indexer and by Stage 1 above 512 blocks.  (Tiles of
 // 64 keys, i.e. twice the barriers, were 2-3 % slower on the 64K flat indexer and 9 % on the 1M
-// chunk.  Measured and not kept: score stores deferred by one iteration so that the wait before
+// chunk; tiles of 256 keys, half the barriers and 128 KB of LDS, 1-2 % faster and not kept.
+// Measured and not kept: score stores deferred by one iteration so that the wait before
 // the barrier finds them old, and on top of that three tile buffers with the LDS operand reads
 // requested one sub-tile early: +2 % and +4 % on the flat indexer, -3 % on short Stage 1 rows.
 // With the DMA, the stores and the barrier all removed the loop itself runs at 1.34 PFLOP/s:
