@@ -1524,6 +1524,10 @@ __global__ __launch_bounds__(512) void k_stage1_query(ScoreArgs a, const void* p
 // (Measured and not kept: the tiles of a query handed out to its waves at run time from an LDS
 // counter instead of dealt round robin, so that the waves finish together: 7-10 % slower with 4
 // waves per query, 2 % with 8, whose waves wait longest for each other.)
+// (Measured and not kept: a grid of as many workgroups as the chip holds, each walking its share
+// of the queries and requesting the next query's fragment and block ids during the top-k of the
+// current one: no faster than the same code with one query per workgroup, and the loop around the
+// kernel body costs 16 % by itself -- 256 registers and spills where this form needs 221.)
 // (Measured and not kept: each workgroup, once its scoring is over, pulling the query of the
 // workgroup 512 or 1024 positions behind it into the XCD's L2: 64K prefill +2 %, 16K -1 %, fp8 keys
 // and the 1M chunk unchanged.  The first read of a query is not what a workgroup waits for.)
