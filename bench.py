@@ -358,9 +358,9 @@ def bench_config(name, steps, warmup, flat_steps, torch, hisa, W, with_flat=True
                 "unit": "TFLOP/s", "kernel": "k_score_ranges_f32 + k_select",
                 "note": "launch-latency bound at this size: three launches of a few microseconds each"}
     elif decode:
-        # every candidate key is read once: the whole step (both stages, four launches) against the HBM peak
+        # every candidate key is read once: the whole step (both stages, three launches) against the HBM peak
         roof = {"bound": "hbm", "achieved": hbm_bytes / (ms_step * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "kernel": "whole step: k_score_ranges + k_select (Stage 1), k_score_ranges + k_select (Stage 2)",
+                "kernel": "whole step: k_stage1_query (Stage 1), k_score_ranges + k_select (Stage 2)",
                 "stage2_scoring_and_select_GBs": (p2 * kbytes + T * (qbytes + wl.m * 4 + wl.k * 4) + 2 * p2 * 4)
                 / (ms_s2 * 1e-3) / 1e9}
     else:
