@@ -129,7 +129,10 @@ int hisa_pool_blocks_max(const hisa_keys* keys, int32_t B, int32_t blk_begin, in
  *   pooled       [n_seq, s_max / B, d] of pooled_dtype (device, in)
  *   block_idx    [T, m] int32 (device, out): kept block ids ascending, then -1
  *   block_scores [T, s_max / B] fp32 (device, out) or NULL: J_{t,b} for b <= b_t, -inf beyond
- * Workspace: T * (s_max / B) floats when block_scores is NULL, else none.
+ * Workspace: T * (s_max / B) floats when block_scores is NULL, else none.  (A batch of at most 256
+ * queries with bf16 pooled keys and at most 8192 blocks per sequence -- a decode step -- is scored
+ * and selected in one launch that keeps the block scores on chip; the workspace must still be
+ * passed, and is then left untouched.)
  */
 int hisa_block_score_topk(const hisa_queries* queries, const hisa_keys* keys, const void* pooled,
                           int32_t pooled_dtype, int32_t B, int32_t m, int32_t* block_idx,
