@@ -427,8 +427,12 @@ int hisa_index_iou(const int32_t* a_idx, const int32_t* b_idx, int32_t T, int32_
                    void* stream) {
   if (!a_idx || !b_idx || !iou) return HISA_ERR_NULL;
   if (T < 1 || k < 1) return HISA_ERR_SHAPE;
-  hipLaunchKernelGGL(k_index_iou, dim3((T + 255) / 256), dim3(256), 0, (hipStream_t)stream, a_idx, b_idx,
-                     T, k, iou);
+  if (k <= 4096)
+    hipLaunchKernelGGL(k_index_iou<true>, dim3((T + 3) / 4), dim3(256), (size_t)4 * k * sizeof(int32_t),
+                       (hipStream_t)stream, a_idx, b_idx, T, k, iou);
+  else
+    hipLaunchKernelGGL(k_index_iou<false>, dim3((T + 3) / 4), dim3(256), 0, (hipStream_t)stream, a_idx, b_idx, T, k,
+                       iou);
   return launch_status();
 }
 

@@ -223,27 +223,46 @@ __global__ __launch_bounds__(256) void k_block_sparse_tokens(ScoreArgs a, int32_
   }
 }
 
-// Eq. 12: one thread per row merges two ascending index rows.
+// Eq. 12: one wave per row.  Both rows are ascending with -1 padding behind the valid entries: the
+// valid lengths are counted, then every lane looks its share of row a up in row b by binary search
+// (a row is a few KB and stays in the L1 / L2 for the walk).
+// STAGED: row b is copied into this wave's k ints of LDS first (k <= 4096), where a probe costs an
+// LDS access instead of a cache access.
+template <bool STAGED>
 __global__ __launch_bounds__(256) void k_index_iou(const int32_t* __restrict__ a_idx,
                                                    const int32_t* __restrict__ b_idx, int T, int k,
                                                    float* __restrict__ iou) {
-  const int t = blockIdx.x * 256 + threadIdx.x;
+  extern __shared__ int32_t iou_rows[];   // STAGED: [4][k]
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
   if (t >= T) return;
   const int32_t* pa = a_idx + (long)t * k;
   const int32_t* pb = b_idx + (long)t * k;
-  int i = 0, j = 0, inter = 0;
-  while (i < k && j < k) {
-    const int x = pa[i], y = pb[j];
-    if (x < 0 || y < 0) break;
-    if (x == y) { ++inter; ++i; ++j; }
-    else if (x < y) ++i;
-    else ++j;
+  int32_t* sb = iou_rows + (threadIdx.x >> 6) * k;
+  // valid lengths: entries in front of the first negative one
+  int first_a = k, first_b = k;
+  for (int i = lane; i < k; i += 64) {
+    const int y = pb[i];
+    if (STAGED) sb[i] = y;
+    if (pa[i] < 0 && i < first_a) first_a = i;
+    if (y < 0 && i < first_b) first_b = i;
   }
-  int na = i, nbv = j;
-  while (na < k && pa[na] >= 0) ++na;
-  while (nbv < k && pb[nbv] >= 0) ++nbv;
-  const int uni = na + nbv - inter;
-  iou[t] = uni == 0 ? 1.f : (float)inter / (float)uni;
+  const int na = k - (int)wave_max((uint32_t)(k - first_a)), nb = k - (int)wave_max((uint32_t)(k - first_b));   // wave minima
+  const int32_t* rb = STAGED ? sb : pb;   // (a wave reads only what it wrote itself: no barrier)
+  int inter = 0;
+  for (int i = lane; i < na; i += 64) {
+    const int x = pa[i];
+    int lo = 0, hi = nb;            // first position of b with b[pos] >= x
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (rb[mid] < x) lo = mid + 1;
+      else hi = mid;
+    }
+    inter += (lo < nb && rb[lo] == x) ? 1 : 0;
+  }
+  inter = (int)wave_sum((uint32_t)inter);
+  const int uni = na + nb - inter;
+  if (lane == 0) iou[t] = uni == 0 ? 1.f : (float)inter / (float)uni;
 }
 
 // ------------------------------------------------------------------------------------------

@@ -277,6 +277,29 @@ def test_block_sparse_tokens_and_iou_diagnostic():
         assert np.all(row[want.size:] == -1), t
         assert abs(iou_h[t] - O.iou(ti_h[t], fi_h[t])) < 1e-6, t
     assert torch.all(hisa.hisa_index_iou(ti, ti) == 1.0)
+    # hand-made rows: both empty (1 by convention), disjoint, nested, partial overlap, full rows of odd width
+    kk = 70
+    a = torch.full((5, kk), -1, dtype=torch.int32)
+    b = torch.full((5, kk), -1, dtype=torch.int32)
+    a[1, :3] = torch.tensor([1, 5, 9]); b[1, :2] = torch.tensor([2, 6])                 # disjoint: 0
+    a[2, :3] = torch.tensor([1, 5, 9]); b[2, :5] = torch.tensor([0, 1, 5, 9, 12])       # nested: 3 / 5
+    a[3, :3] = torch.tensor([1, 5, 9]); b[3, :4] = torch.tensor([5, 7, 9, 11])          # 2 / 5
+    a[4] = torch.arange(0, 2 * kk, 2, dtype=torch.int32); b[4] = torch.arange(0, 3 * kk, 3, dtype=torch.int32)
+    got = hisa.hisa_index_iou(a.cuda(), b.cuda()).cpu().numpy()
+    want = [1.0, 0.0, 0.6, 0.4, O.iou(a[4].numpy(), b[4].numpy())]
+    assert np.allclose(got, want, atol=1e-6), (got, want)
+    # rows wider than the kernel stages in LDS (k > 4096), ragged valid lengths
+    kw = 5000
+    rng = np.random.default_rng(3)
+    aw = np.full((6, kw), -1, dtype=np.int32)
+    bw = np.full((6, kw), -1, dtype=np.int32)
+    for r in range(6):
+        na, nb = int(rng.integers(0, kw + 1)), int(rng.integers(0, kw + 1))
+        aw[r, :na] = np.sort(rng.choice(20000, size=na, replace=False))
+        bw[r, :nb] = np.sort(rng.choice(20000, size=nb, replace=False))
+    got = hisa.hisa_index_iou(torch.from_numpy(aw).cuda(), torch.from_numpy(bw).cuda()).cpu().numpy()
+    want = [O.iou(aw[r], bw[r]) for r in range(6)]
+    assert np.allclose(got, want, atol=1e-6), (got, want)
 
 
 def test_bad_device_side_metadata_stays_in_bounds():
