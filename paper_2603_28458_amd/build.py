@@ -34,7 +34,34 @@ def build(verbose: bool = True) -> str:
         raise RuntimeError(f"hipcc failed ({res.returncode}):\n{res.stdout}\n{err}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
+    try:
+        build_example(verbose=verbose)
+    except (RuntimeError, OSError) as e:     # the example is an illustration: the library stands without it
+        print(f"warning: the C example was not built: {e}", file=sys.stderr)
     return LIB_PATH
+
+
+EXAMPLE_SRC = os.path.join(CSRC, "example_decode.c")
+EXAMPLE_PATH = os.path.join(LIB_DIR, "example_decode")
+
+
+def example_command(out_path: str) -> list:
+    """The gcc line that compiles the plain-C example against the header and links it with the
+    library and the HIP runtime."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    return ["gcc", "-std=c11", "-O1", "-Wall", "-Werror", "-D__HIP_PLATFORM_AMD__", f"-I{rocm}/include",
+            f"-I{os.path.join(os.path.dirname(HERE), 'include')}", EXAMPLE_SRC, f"-L{LIB_DIR}", "-lhisa",
+            f"-L{rocm}/lib", "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN", f"-Wl,-rpath,{rocm}/lib", "-o", out_path]
+
+
+def build_example(verbose: bool = True, out_path: str = EXAMPLE_PATH) -> str:
+    cmd = example_command(out_path)
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"gcc failed on the C example ({res.returncode}):\n{res.stdout}\n{res.stderr}")
+    return out_path
 
 
 if __name__ == "__main__":

@@ -175,3 +175,19 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(hisa, "LIB_PATH", "/nonexistent/libhisa.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         hisa.lib()
+
+
+def test_the_header_is_valid_c_and_the_plain_c_example_links(tmp_path):
+    """include/hisa.h is a C header: the example program is C11, compiled by gcc with warnings as
+    errors, and links against the library and the HIP runtime (nothing is run here)."""
+    import shutil
+    import subprocess
+    from paper_2603_28458_amd import build as B
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    if not os.path.exists(B.LIB_PATH):
+        pytest.skip("library not built")
+    out = str(tmp_path / "example_decode")
+    res = subprocess.run(B.example_command(out), capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+    assert os.path.exists(out)
