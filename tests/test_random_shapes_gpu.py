@@ -50,3 +50,27 @@ def test_random_shapes(stream):
         print(f"\n[parity] {wl.name}: mode={mode} T={wl.T} H={wl.H} d={wl.d} B={wl.B} m={wl.m} k={wl.k} "
               f"k={wl.k_dtype} n_seq={wl.n_seq} s_max={wl.s_max} seed={wl.seed}", flush=True)
         run_and_check(wl, queries=sample_queries(wl, 40, seed=case))
+
+
+def test_random_small_batches_against_long_contexts():
+    """Up to 256 queries against up to hundreds of thousands of keys (a chunk at the end of a long
+    prefix, or a decode batch of up to 39 ragged sequences): the shapes whose Stage 1 runs in one
+    launch per batch, with up to 8000 blocks per sequence, and whose Stage 2 takes the two-kernel path."""
+    rng = np.random.default_rng(21)
+    for case in range(16):
+        H, B = int(rng.choice([32, 64])), int(rng.choice([32, 64, 128]))
+        kd = str(rng.choice(["bf16", "fp8_e4m3"]))
+        m = int(rng.integers(2, 65))
+        k = min(int(rng.integers(1, m * B + 1)), 2048)
+        if rng.random() < 0.5:
+            L = int(rng.integers(B, 260000 if B == 32 else 400000))
+            kw = dict(n_seq=1, seq_len=L, T=int(rng.integers(1, 257)), mode="prefill")
+        else:
+            n = int(rng.integers(1, 40))
+            top = int(rng.integers(2000, 120000))
+            kw = dict(n_seq=n, seq_len=[int(rng.integers(1, top)) for _ in range(n)], T=n, mode="decode")
+        wl = W.make_workload(f"small{case}", H=H, d=128, B=B, m=m, k=k, q_dtype="bf16", k_dtype=kd,
+                             seed=21000 + case, **kw)
+        print(f"\n[parity] {wl.name}: T={wl.T} H={H} B={B} m={m} k={k} k={kd} n_seq={wl.n_seq} s_max={wl.s_max} "
+              f"blocks={wl.s_max // B}", flush=True)
+        run_and_check(wl, queries=sample_queries(wl, 24, seed=case), check_flat=wl.s_max <= 70000)
